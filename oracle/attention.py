@@ -1,0 +1,69 @@
+"""Dense softmax attention over packed variable-length sequences (oracle).
+
+Each sequence attends only to itself; a decoder section masks keys after the
+query (causal), an encoder section does not (the vision encoder of the paper's
+Sec. 2.1 attends over the whole visual sequence).  Query head h reads KV head
+h // (n_q / n_kv) (grouped-query attention).  The full L x L score matrix is
+formed per sequence and head: this is the definition the tiled HIP kernels
+re-associate.
+"""
+import numpy as np
+
+
+def _softmax_rows(s):
+    m = np.max(s, axis=1, keepdims=True)
+    e = np.exp(s - m)
+    return e / np.sum(e, axis=1, keepdims=True)
+
+
+def _probs(qh, kh, causal):
+    L, hd = qh.shape
+    s = (qh @ kh.T) / np.sqrt(float(hd))
+    if causal:
+        s = np.where(np.tril(np.ones((L, L), dtype=bool)), s, -np.inf)
+    return _softmax_rows(s)
+
+
+def attention_fwd(q, k, v, cu_seqlens, causal):
+    """q[N, nq, hd], k/v[N, nkv, hd] -> o[N, nq, hd]."""
+    n, nq, hd = q.shape
+    nkv = k.shape[1]
+    grp = nq // nkv
+    o = np.zeros_like(q)
+    cu = np.asarray(cu_seqlens, dtype=np.int64)
+    for b in range(len(cu) - 1):
+        s0, s1 = int(cu[b]), int(cu[b + 1])
+        if s1 == s0:
+            continue
+        for h in range(nq):
+            p = _probs(q[s0:s1, h], k[s0:s1, h // grp], causal)
+            o[s0:s1, h] = p @ v[s0:s1, h // grp]
+    return o
+
+
+def attention_bwd(do, q, k, v, cu_seqlens, causal):
+    """Gradients of attention_fwd: dV = P^T dO, dP = dO V^T,
+    dS = P * (dP - rowsum(dP * P)), dQ = dS K / sqrt(hd), dK = dS^T Q / sqrt(hd);
+    dK and dV are summed over the query heads that share a KV head."""
+    n, nq, hd = q.shape
+    nkv = k.shape[1]
+    grp = nq // nkv
+    dq = np.zeros_like(q)
+    dk = np.zeros_like(k)
+    dv = np.zeros_like(v)
+    cu = np.asarray(cu_seqlens, dtype=np.int64)
+    scale = 1.0 / np.sqrt(float(hd))
+    for b in range(len(cu) - 1):
+        s0, s1 = int(cu[b]), int(cu[b + 1])
+        if s1 == s0:
+            continue
+        for h in range(nq):
+            g = h // grp
+            p = _probs(q[s0:s1, h], k[s0:s1, g], causal)
+            doh = do[s0:s1, h]
+            dv[s0:s1, g] += p.T @ doh
+            dp = doh @ v[s0:s1, g].T
+            ds = p * (dp - np.sum(dp * p, axis=1, keepdims=True))
+            dq[s0:s1, h] = (ds @ k[s0:s1, g]) * scale
+            dk[s0:s1, g] += (ds.T @ q[s0:s1, h]) * scale
+    return dq, dk, dv

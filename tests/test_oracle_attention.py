@@ -1,0 +1,114 @@
+"""Pins for the oracle's dense variable-length attention."""
+import math
+
+import numpy as np
+import pytest
+
+from oracle.attention import attention_bwd, attention_fwd
+from conftest import fd_grad
+
+
+def _brute(q, k, v, cu, causal):
+    n, nq, hd = q.shape
+    grp = nq // k.shape[1]
+    o = np.zeros_like(q)
+    for b in range(len(cu) - 1):
+        for i in range(cu[b], cu[b + 1]):
+            for h in range(nq):
+                last = i if causal else cu[b + 1] - 1
+                s = [sum(q[i, h, d] * k[j, h // grp, d] for d in range(hd)) / math.sqrt(hd)
+                     for j in range(cu[b], last + 1)]
+                m = max(s)
+                e = [math.exp(x - m) for x in s]
+                z = sum(e)
+                for d in range(hd):
+                    o[i, h, d] = sum(e[jj] / z * v[cu[b] + jj, h // grp, d] for jj in range(len(s)))
+    return o
+
+
+@pytest.mark.parametrize("causal", [True, False])
+def test_brute_force_tiny(rng, causal):
+    cu = [0, 3, 4, 9]
+    q, k, v = rng.standard_normal((9, 4, 4)), rng.standard_normal((9, 2, 4)), rng.standard_normal((9, 2, 4))
+    assert np.allclose(attention_fwd(q, k, v, cu, causal), _brute(q, k, v, cu, causal), atol=1e-13)
+
+
+def test_length_one_and_equal_keys(rng):
+    q, k, v = rng.standard_normal((1, 2, 8)), rng.standard_normal((1, 2, 8)), rng.standard_normal((1, 2, 8))
+    assert np.allclose(attention_fwd(q, k, v, [0, 1], True), v)
+    L = 6
+    q, v = rng.standard_normal((L, 1, 8)), rng.standard_normal((L, 1, 8))
+    k = np.tile(rng.standard_normal((1, 1, 8)), (L, 1, 1))
+    oc = attention_fwd(q, k, v, [0, L], True)
+    ob = attention_fwd(q, k, v, [0, L], False)
+    for i in range(L):
+        assert np.allclose(oc[i, 0], v[:i + 1, 0].mean(axis=0))                 # running mean
+        assert np.allclose(ob[i, 0], v[:, 0].mean(axis=0))
+
+
+def test_causality_is_bit_exact(rng):
+    q, k, v = rng.standard_normal((10, 2, 8)), rng.standard_normal((10, 2, 8)), rng.standard_normal((10, 2, 8))
+    o1 = attention_fwd(q, k, v, [0, 10], True)
+    q2, k2, v2 = q.copy(), k.copy(), v.copy()
+    q2[6:] += 1.0; k2[6:] -= 2.0; v2[6:] *= 3.0
+    o2 = attention_fwd(q2, k2, v2, [0, 10], True)
+    assert np.array_equal(o1[:6], o2[:6]) and not np.allclose(o1[6:], o2[6:])
+    ob1 = attention_fwd(q, k, v, [0, 10], False)
+    ob2 = attention_fwd(q, k2, v2, [0, 10], False)
+    assert not np.allclose(ob1[:6], ob2[:6])                                    # encoder does look ahead
+
+
+@pytest.mark.parametrize("causal", [True, False])
+def test_packed_equals_separate_and_no_cross_talk(rng, causal):
+    lens = [5, 1, 7]
+    cu = np.concatenate([[0], np.cumsum(lens)])
+    q, k, v = rng.standard_normal((13, 4, 8)), rng.standard_normal((13, 2, 8)), rng.standard_normal((13, 2, 8))
+    o = attention_fwd(q, k, v, cu, causal)
+    for b in range(3):
+        s = slice(cu[b], cu[b + 1])
+        assert np.array_equal(o[s], attention_fwd(q[s], k[s], v[s], [0, lens[b]], causal))
+    # zero-length entries in cu_seqlens are legal and change nothing
+    assert np.array_equal(o, attention_fwd(q, k, v, [0, 5, 5, 6, 13, 13], causal))
+
+
+def test_gqa_equals_mha_with_replicated_kv(rng):
+    q, k, v = rng.standard_normal((7, 6, 4)), rng.standard_normal((7, 2, 4)), rng.standard_normal((7, 2, 4))
+    kr, vr = np.repeat(k, 3, axis=1), np.repeat(v, 3, axis=1)
+    assert np.allclose(attention_fwd(q, k, v, [0, 7], True), attention_fwd(q, kr, vr, [0, 7], True), atol=1e-15)
+    do = rng.standard_normal((7, 6, 4))
+    dq, dk, dv = attention_bwd(do, q, k, v, [0, 7], True)
+    dq2, dk2, dv2 = attention_bwd(do, q, kr, vr, [0, 7], True)
+    assert np.allclose(dq, dq2)
+    assert np.allclose(dk, dk2.reshape(7, 2, 3, 4).sum(axis=2))                 # group sum
+    assert np.allclose(dv, dv2.reshape(7, 2, 3, 4).sum(axis=2))
+
+
+def test_encoder_is_permutation_equivariant(rng):
+    q, k, v = rng.standard_normal((8, 2, 4)), rng.standard_normal((8, 2, 4)), rng.standard_normal((8, 2, 4))
+    perm = rng.permutation(8)
+    o = attention_fwd(q, k, v, [0, 8], False)
+    op = attention_fwd(q[perm], k[perm], v[perm], [0, 8], False)
+    assert np.allclose(o[perm], op, atol=1e-14)
+
+
+def test_sharp_scores_stay_finite(rng):
+    q, k, v = 60 * rng.standard_normal((12, 1, 8)), 60 * rng.standard_normal((12, 1, 8)), rng.standard_normal((12, 1, 8))
+    o = attention_fwd(q, k, v, [0, 12], False)
+    assert np.all(np.isfinite(o))
+    # near one-hot rows: each output is (almost) one of the value rows
+    d = np.abs(o[:, 0, None, :] - v[None, :, 0, :]).max(axis=2).min(axis=1)
+    assert np.all(d < 1e-6)
+
+
+@pytest.mark.parametrize("causal", [True, False])
+def test_backward_finite_difference(rng, causal):
+    cu = [0, 4, 9]
+    q, k, v = rng.standard_normal((9, 4, 4)), rng.standard_normal((9, 2, 4)), rng.standard_normal((9, 2, 4))
+    c = rng.standard_normal((9, 4, 4))
+    f = lambda: float(np.sum(c * attention_fwd(q, k, v, cu, causal)))
+    dq, dk, dv = attention_bwd(c, q, k, v, cu, causal)
+    for idx in [(0, 0, 0), (3, 1, 2), (5, 3, 1), (8, 2, 3)]:
+        assert dq[idx] == pytest.approx(fd_grad(f, q, idx), rel=1e-6, abs=1e-9)
+    for idx in [(0, 0, 0), (3, 1, 2), (5, 0, 1), (8, 1, 3)]:
+        assert dk[idx] == pytest.approx(fd_grad(f, k, idx), rel=1e-6, abs=1e-9)
+        assert dv[idx] == pytest.approx(fd_grad(f, v, idx), rel=1e-6, abs=1e-9)
