@@ -1,0 +1,99 @@
+/*
+ * maestro_kernels.h -- kernel-level entry points of the section-compute library.
+ *
+ * These are the individual steps that ms_section_forward / ms_section_forward_backward /
+ * ms_kd_loss_forward_backward (maestro_section.h) are composed of, exported so that each
+ * kernel can be checked against the CPU oracle and timed against its roofline on its own.
+ * The paper inherits its per-GPU layer compute from an existing framework and describes
+ * none of it (Sec. 4, experimental setup); the operations are the textbook definitions
+ * fixed by the workload shapes.  Same conventions as maestro_section.h: all data
+ * pointers are device memory owned by the caller, `dtype` is an ms_dtype (bf16 storage
+ * with fp32 math, or fp32), calls enqueue on `stream` and return an ms_status.
+ */
+#ifndef MAESTRO_KERNELS_H
+#define MAESTRO_KERNELS_H
+
+#include "maestro_section.h"
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+/* C[M,N] = alpha * sum_k A(m,k) B(n,k) (+ bias[n]) (+ residual[m,n]), optionally C += .
+ * trans_a = 0: A is [M,K] row-major (lda); 1: A is stored [K,M] (lda).
+ * trans_b = 0: B is [N,K] row-major (ldb); 1: B is stored [K,N] (ldb).
+ * c_fp32: C is fp32 regardless of dtype.  accumulate (needs c_fp32): C += result; with
+ * split_k > 1 the K range is divided over that many workgroups that add atomically.
+ * bias / residual are `dtype` (NULL = none), residual has leading dimension ldr.
+ * bf16 needs K % 8 == 0 for a non-transposed operand, M (resp. N) % 8 == 0 for a
+ * transposed one, and 16-byte aligned rows. */
+ms_status ms_k_gemm(int32_t dtype, int32_t trans_a, int32_t trans_b, int32_t M, int32_t N, int32_t K,
+                    float alpha, const void *A, int64_t lda, const void *B, int64_t ldb, void *C,
+                    int64_t ldc, int32_t c_fp32, int32_t accumulate, const void *bias,
+                    const void *residual, int64_t ldr, int32_t split_k, void *stream);
+
+/* kind 0: RMSNorm y = x rstd g; kind 1: LayerNorm y = (x - mean) rstd g + b.
+ * mean (kind 1 only) and rstd are fp32 [n] outputs kept for the backward pass. */
+ms_status ms_k_norm_forward(int32_t kind, int32_t dtype, int32_t n, int32_t d, float eps,
+                            const void *x, const void *g, const void *b, void *y, float *mean,
+                            float *rstd, void *stream);
+/* dx = norm backward of dy (+ add, if add != NULL);  dg += sum_t dy xhat;  db += sum_t dy.
+ * dg / db fp32 [d], accumulated.  scratch: fp32, ms_k_norm_backward_scratch_bytes(d). */
+size_t ms_k_norm_backward_scratch_bytes(int32_t d);
+ms_status ms_k_norm_backward(int32_t kind, int32_t dtype, int32_t n, int32_t d, const void *dy,
+                             const void *x, const void *g, const float *mean, const float *rstd,
+                             const void *add, void *dx, float *dg, float *db, void *scratch,
+                             void *stream);
+
+/* pos[t] = t - cu_seqlens[b(t)]: position of each packed token inside its sequence. */
+ms_status ms_k_positions(int32_t n_tokens, int32_t n_seqs, const int32_t *cu_seqlens, int32_t *pos,
+                         void *stream);
+/* table[p, i] = (cos, sin)(p * base^(-2i/head_dim)), p < max_pos, i < head_dim/2; angles in fp64. */
+ms_status ms_k_rope_table(int32_t max_pos, int32_t head_dim, float base, float *table, void *stream);
+/* In-place half-split rotary embedding of the first n_heads heads of every row of
+ * x[n, row_stride]; inverse != 0 rotates by the negative angle (backward pass). */
+ms_status ms_k_rope(int32_t dtype, int32_t n, int32_t n_heads, int32_t head_dim, int64_t row_stride,
+                    void *x, const int32_t *pos, const float *table, int32_t inverse, void *stream);
+
+/* kind 0 SwiGLU: up[n, 2f] = [gate | up] -> a[n, f] = silu(gate) * up.
+ * kind 1 GELU (erf): up[n, f] -> a[n, f]. */
+ms_status ms_k_act_forward(int32_t kind, int32_t dtype, int32_t n, int32_t f, const void *up, void *a,
+                           void *stream);
+ms_status ms_k_act_backward(int32_t kind, int32_t dtype, int32_t n, int32_t f, const void *da,
+                            const void *up, void *dup, void *stream);
+
+ms_status ms_k_embedding_forward(int32_t dtype, int32_t n, int32_t d, int32_t vocab, const int32_t *ids,
+                                 const void *table, void *x, void *stream);
+/* d_table[ids[t], :] += dx[t, :]  (fp32, atomic). */
+ms_status ms_k_embedding_backward(int32_t dtype, int32_t n, int32_t d, int32_t vocab, const int32_t *ids,
+                                  const void *dx, float *d_table, void *stream);
+
+/* out[j] += sum_t x[t, j]  (fp32 [c], accumulated).  scratch as for the norm backward with d = c. */
+ms_status ms_k_colsum(int32_t dtype, int32_t n, int32_t c, const void *x, float *out, void *scratch,
+                      void *stream);
+
+/* Softmax attention per sequence on packed tokens.  qkv[n, (nq + 2 nkv) hd]: per row all Q
+ * heads, all K heads, all V heads.  o[n, nq hd].  lse[nq, n] fp32 = log-sum-exp of the scaled
+ * scores (kept for the backward pass).  causal != 0 masks keys after the query.
+ * max_seqlen: upper bound of the sequence lengths in cu_seqlens (sizes the launch). */
+ms_status ms_k_attention_forward(int32_t dtype, int32_t causal, int32_t n_q_heads, int32_t n_kv_heads,
+                                 int32_t head_dim, int32_t n_tokens, int32_t n_seqs, int32_t max_seqlen,
+                                 const int32_t *cu_seqlens, const void *qkv, void *o, float *lse,
+                                 void *stream);
+/* dqkv[n, (nq + 2 nkv) hd] from d_o, with dK / dV summed over each KV head's query group.
+ * scratch: ms_k_attention_backward_scratch_bytes(...) bytes. */
+size_t ms_k_attention_backward_scratch_bytes(int32_t dtype, int32_t n_q_heads, int32_t n_kv_heads,
+                                             int32_t head_dim, int32_t n_tokens);
+ms_status ms_k_attention_backward(int32_t dtype, int32_t causal, int32_t n_q_heads, int32_t n_kv_heads,
+                                  int32_t head_dim, int32_t n_tokens, int32_t n_seqs, int32_t max_seqlen,
+                                  const int32_t *cu_seqlens, const void *qkv, const void *o,
+                                  const float *lse, const void *d_o, void *dqkv, void *scratch,
+                                  void *stream);
+
+/* Plain device copy of `bytes` bytes (a known-traffic kernel for calibrating counters). */
+ms_status ms_k_copy(const void *src, void *dst, size_t bytes, void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif

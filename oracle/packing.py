@@ -2,7 +2,7 @@
 
 A sample whose length for this section is zero does not activate the section
 and is dropped (a text-only sample bypasses the vision encoder: paper Sec. 2.1
-and the worked example of Sec. 3.3, where a zero time before the critical
+and the worked example of Sec. 3.4, where a zero time before the critical
 section marks such a sample).  The remaining samples are taken in the given
 order, or longest first, and packed greedily under a per-section token budget
 (each section has its own micro-batch size: Sec. 3.2).

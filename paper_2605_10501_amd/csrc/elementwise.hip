@@ -1,0 +1,572 @@
+// HBM-bound kernels of the section path: norms, rotary embedding, activations, embedding,
+// column sums, fills and conversions.  Every kernel moves 16-byte vectors per lane, does its
+// arithmetic in fp32 and touches each element once; rows are reduced with wave shuffles.
+#include "common.h"
+#include "launch.h"
+
+namespace {
+
+constexpr int kMaxCache = 8;       // 16-byte vectors a lane keeps in registers per row
+constexpr int kPartialRows = 1024; // rows of the partial-sum scratch of column reductions
+
+// ------------------------------------------------------------------ norm forward
+template <class T, int KIND>
+__global__ __launch_bounds__(256) void norm_fwd_kernel(const T *__restrict__ x, const T *__restrict__ g,
+                                                        const T *__restrict__ b, T *__restrict__ y,
+                                                        float *__restrict__ mean, float *__restrict__ rstd,
+                                                        int n, int d, float eps) {
+    constexpr int V = Vec16<T>::N;
+    const int lane = threadIdx.x & 63;
+    const int row = blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (row >= n) return;
+    const T *xr = x + (size_t)row * d;
+    T *yr = y + (size_t)row * d;
+    const int nvec = d / V;
+    Vec16<T> cache[kMaxCache];
+    float s = 0.f, ss = 0.f;
+#pragma unroll
+    for (int i = 0; i < kMaxCache; ++i) {
+        int idx = lane + 64 * i;
+        if (idx < nvec) {
+            cache[i] = ldv(xr + (size_t)idx * V);
+#pragma unroll
+            for (int e = 0; e < V; ++e) {
+                float f = to_f32(cache[i].v[e]);
+                s += f;
+                ss += f * f;
+            }
+        }
+    }
+    for (int idx = lane + 64 * kMaxCache; idx < nvec; idx += 64) {
+        Vec16<T> t = ldv(xr + (size_t)idx * V);
+#pragma unroll
+        for (int e = 0; e < V; ++e) {
+            float f = to_f32(t.v[e]);
+            s += f;
+            ss += f * f;
+        }
+    }
+    float mu = 0.f, var;
+    if (KIND == 1) {
+        mu = wave_sum(s) / d;
+        float sq = 0.f;  // second pass over the cached row: sum (x - mu)^2
+#pragma unroll
+        for (int i = 0; i < kMaxCache; ++i) {
+            int idx = lane + 64 * i;
+            if (idx < nvec) {
+#pragma unroll
+                for (int e = 0; e < V; ++e) {
+                    float f = to_f32(cache[i].v[e]) - mu;
+                    sq += f * f;
+                }
+            }
+        }
+        for (int idx = lane + 64 * kMaxCache; idx < nvec; idx += 64) {
+            Vec16<T> t = ldv(xr + (size_t)idx * V);
+#pragma unroll
+            for (int e = 0; e < V; ++e) {
+                float f = to_f32(t.v[e]) - mu;
+                sq += f * f;
+            }
+        }
+        var = wave_sum(sq) / d;
+    } else {
+        var = wave_sum(ss) / d;
+    }
+    const float r = rsqrtf(var + eps);
+    if (lane == 0) {
+        rstd[row] = r;
+        if (KIND == 1) mean[row] = mu;
+    }
+    auto emit = [&](int idx, const Vec16<T> &xv) {
+        Vec16<T> gv = ldv(g + (size_t)idx * V), bv, out;
+        if (KIND == 1) bv = ldv(b + (size_t)idx * V);
+#pragma unroll
+        for (int e = 0; e < V; ++e) {
+            float f = (to_f32(xv.v[e]) - mu) * r * to_f32(gv.v[e]);
+            if (KIND == 1) f += to_f32(bv.v[e]);
+            out.v[e] = from_f32<T>(f);
+        }
+        stv(yr + (size_t)idx * V, out);
+    };
+#pragma unroll
+    for (int i = 0; i < kMaxCache; ++i) {
+        int idx = lane + 64 * i;
+        if (idx < nvec) emit(idx, cache[i]);
+    }
+    for (int idx = lane + 64 * kMaxCache; idx < nvec; idx += 64) emit(idx, ldv(xr + (size_t)idx * V));
+}
+
+// ------------------------------------------------------------------ norm backward
+// One wave per row, rows strided over the grid; each lane keeps the dg (and db) sums of its
+// columns in registers and finally writes one partial row per wave.
+template <class T, int KIND>
+__global__ __launch_bounds__(256) void norm_bwd_kernel(const T *__restrict__ dy, const T *__restrict__ x,
+                                                        const T *__restrict__ g, const float *__restrict__ mean,
+                                                        const float *__restrict__ rstd, const T *__restrict__ add,
+                                                        T *__restrict__ dx, float *__restrict__ part_g,
+                                                        float *__restrict__ part_b, int n, int d) {
+    constexpr int V = Vec16<T>::N;
+    const int lane = threadIdx.x & 63;
+    const int w = blockIdx.x * 4 + (threadIdx.x >> 6);
+    const int nw = gridDim.x * 4;
+    const int nvec = d / V;
+    float accg[kMaxCache][V], accb[KIND == 1 ? kMaxCache : 1][V];
+    Vec16<T> gv[kMaxCache];
+#pragma unroll
+    for (int i = 0; i < kMaxCache; ++i) {
+        int idx = lane + 64 * i;
+        if (idx < nvec) gv[i] = ldv(g + (size_t)idx * V);
+#pragma unroll
+        for (int e = 0; e < V; ++e) {
+            accg[i][e] = 0.f;
+            if constexpr (KIND == 1) accb[i][e] = 0.f;
+        }
+    }
+    for (int row = w; row < n; row += nw) {
+        const size_t ro = (size_t)row * d;
+        const float r = rstd[row];
+        const float mu = KIND == 1 ? mean[row] : 0.f;
+        Vec16<T> xv[kMaxCache], dv[kMaxCache];
+        float c1 = 0.f, c2 = 0.f;
+#pragma unroll
+        for (int i = 0; i < kMaxCache; ++i) {
+            int idx = lane + 64 * i;
+            if (idx < nvec) {
+                xv[i] = ldv(x + ro + (size_t)idx * V);
+                dv[i] = ldv(dy + ro + (size_t)idx * V);
+#pragma unroll
+                for (int e = 0; e < V; ++e) {
+                    float xh = (to_f32(xv[i].v[e]) - mu) * r;
+                    float dyv = to_f32(dv[i].v[e]);
+                    float t = dyv * to_f32(gv[i].v[e]);
+                    c1 += t * xh;
+                    c2 += t;
+                    accg[i][e] += dyv * xh;
+                    if constexpr (KIND == 1) accb[i][e] += dyv;
+                }
+            }
+        }
+        c1 = wave_sum(c1) / d;
+        c2 = KIND == 1 ? wave_sum(c2) / d : 0.f;
+#pragma unroll
+        for (int i = 0; i < kMaxCache; ++i) {
+            int idx = lane + 64 * i;
+            if (idx < nvec) {
+                Vec16<T> av, out;
+                if (add) av = ldv(add + ro + (size_t)idx * V);
+#pragma unroll
+                for (int e = 0; e < V; ++e) {
+                    float xh = (to_f32(xv[i].v[e]) - mu) * r;
+                    float t = to_f32(dv[i].v[e]) * to_f32(gv[i].v[e]);
+                    float f = r * (t - c2 - xh * c1);
+                    if (add) f += to_f32(av.v[e]);
+                    out.v[e] = from_f32<T>(f);
+                }
+                stv(dx + ro + (size_t)idx * V, out);
+            }
+        }
+    }
+#pragma unroll
+    for (int i = 0; i < kMaxCache; ++i) {
+        int idx = lane + 64 * i;
+        if (idx < nvec) {
+#pragma unroll
+            for (int e = 0; e < V; ++e) {
+                part_g[(size_t)w * d + idx * V + e] = accg[i][e];
+                if constexpr (KIND == 1) part_b[(size_t)w * d + idx * V + e] = accb[i][e];
+            }
+        }
+    }
+}
+
+// out[j] += sum_p part[p, j]; block = 64 columns x 4 row lanes.
+__global__ __launch_bounds__(256) void reduce_partials_kernel(const float *__restrict__ part, int np, int c,
+                                                               float *__restrict__ out) {
+    __shared__ float sm[4][64];
+    const int col = blockIdx.x * 64 + (threadIdx.x & 63);
+    const int pl = threadIdx.x >> 6;
+    float s = 0.f;
+    if (col < c)
+        for (int p = pl; p < np; p += 4) s += part[(size_t)p * c + col];
+    sm[pl][threadIdx.x & 63] = s;
+    __syncthreads();
+    if (pl == 0 && col < c) out[col] += sm[0][threadIdx.x] + sm[1][threadIdx.x] + sm[2][threadIdx.x] + sm[3][threadIdx.x];
+}
+
+// partial column sums: lane <-> one 16-byte column vector, waves stride over rows.
+template <class T>
+__global__ __launch_bounds__(256) void colsum_partial_kernel(const T *__restrict__ x, int n, int c,
+                                                              float *__restrict__ part) {
+    constexpr int V = Vec16<T>::N;
+    const int cv = blockIdx.x * 64 + (threadIdx.x & 63);
+    const int w = blockIdx.y * 4 + (threadIdx.x >> 6);
+    const int nw = gridDim.y * 4;
+    if (cv * V >= c) return;
+    float acc[V];
+#pragma unroll
+    for (int e = 0; e < V; ++e) acc[e] = 0.f;
+    for (int row = w; row < n; row += nw) {
+        Vec16<T> t = ldv(x + (size_t)row * c + (size_t)cv * V);
+#pragma unroll
+        for (int e = 0; e < V; ++e) acc[e] += to_f32(t.v[e]);
+    }
+#pragma unroll
+    for (int e = 0; e < V; ++e) part[(size_t)w * c + cv * V + e] = acc[e];
+}
+
+// ------------------------------------------------------------------ rotary embedding
+__global__ void positions_kernel(int n, int n_seqs, const int *__restrict__ cu, int *__restrict__ pos) {
+    int t = blockIdx.x * blockDim.x + threadIdx.x;
+    if (t >= n) return;
+    int lo = 0, hi = n_seqs;  // largest b with cu[b] <= t
+    while (hi - lo > 1) {
+        int mid = (lo + hi) >> 1;
+        if (cu[mid] <= t) lo = mid; else hi = mid;
+    }
+    pos[t] = t - cu[lo];
+}
+
+__global__ void rope_table_kernel(int max_pos, int half, int hd, double base, float2 *__restrict__ table) {
+    int idx = blockIdx.x * blockDim.x + threadIdx.x;
+    if (idx >= max_pos * half) return;
+    int p = idx / half, i = idx % half;
+    double ang = (double)p * pow(base, -2.0 * (double)i / (double)hd);
+    table[idx] = make_float2((float)cos(ang), (float)sin(ang));
+}
+
+template <class T>
+__global__ __launch_bounds__(256) void rope_kernel(T *__restrict__ x, const int *__restrict__ pos,
+                                                   const float2 *__restrict__ table, long total, int n_heads,
+                                                   int hd, long row_stride, float sign) {
+    constexpr int V = Vec16<T>::N;
+    const int half = hd / 2, vph = half / V;
+    long idx = (long)blockIdx.x * blockDim.x + threadIdx.x;
+    if (idx >= total) return;
+    int iv = idx % vph;
+    long th = idx / vph;
+    int h = th % n_heads;
+    long t = th / n_heads;
+    T *p = x + t * row_stride + (long)h * hd + iv * V;
+    const float2 *cs = table + (long)pos[t] * half + iv * V;
+    Vec16<T> lo = ldv(p), hi = ldv(p + half), olo, ohi;
+#pragma unroll
+    for (int e = 0; e < V; ++e) {
+        float c = cs[e].x, s = sign * cs[e].y;
+        float a = to_f32(lo.v[e]), b = to_f32(hi.v[e]);
+        olo.v[e] = from_f32<T>(a * c - b * s);
+        ohi.v[e] = from_f32<T>(b * c + a * s);
+    }
+    stv(p, olo);
+    stv(p + half, ohi);
+}
+
+// ------------------------------------------------------------------ activations
+template <class T, int KIND>
+__global__ __launch_bounds__(256) void act_fwd_kernel(const T *__restrict__ up, T *__restrict__ a, long nvec_total,
+                                                      int f) {
+    constexpr int V = Vec16<T>::N;
+    long idx = (long)blockIdx.x * blockDim.x + threadIdx.x;
+    if (idx >= nvec_total) return;
+    const int vpr = f / V;
+    long row = idx / vpr;
+    int cv = idx % vpr;
+    Vec16<T> out;
+    if (KIND == 0) {
+        const T *base = up + row * 2 * f + (long)cv * V;
+        Vec16<T> gv = ldv(base), uv = ldv(base + f);
+#pragma unroll
+        for (int e = 0; e < V; ++e) {
+            float gg = to_f32(gv.v[e]);
+            out.v[e] = from_f32<T>(gg / (1.f + __expf(-gg)) * to_f32(uv.v[e]));
+        }
+    } else {
+        Vec16<T> xv = ldv(up + row * f + (long)cv * V);
+#pragma unroll
+        for (int e = 0; e < V; ++e) {
+            float xx = to_f32(xv.v[e]);
+            out.v[e] = from_f32<T>(0.5f * xx * (1.f + erff(xx * 0.70710678118654752f)));
+        }
+    }
+    stv(a + row * f + (long)cv * V, out);
+}
+
+template <class T, int KIND>
+__global__ __launch_bounds__(256) void act_bwd_kernel(const T *__restrict__ da, const T *__restrict__ up,
+                                                      T *__restrict__ dup, long nvec_total, int f) {
+    constexpr int V = Vec16<T>::N;
+    long idx = (long)blockIdx.x * blockDim.x + threadIdx.x;
+    if (idx >= nvec_total) return;
+    const int vpr = f / V;
+    long row = idx / vpr;
+    int cv = idx % vpr;
+    Vec16<T> dav = ldv(da + row * f + (long)cv * V);
+    if (KIND == 0) {
+        const T *base = up + row * 2 * f + (long)cv * V;
+        Vec16<T> gv = ldv(base), uv = ldv(base + f), dg, du;
+#pragma unroll
+        for (int e = 0; e < V; ++e) {
+            float gg = to_f32(gv.v[e]), uu = to_f32(uv.v[e]), d = to_f32(dav.v[e]);
+            float s = 1.f / (1.f + __expf(-gg));
+            dg.v[e] = from_f32<T>(d * uu * s * (1.f + gg * (1.f - s)));
+            du.v[e] = from_f32<T>(d * gg * s);
+        }
+        T *ob = dup + row * 2 * f + (long)cv * V;
+        stv(ob, dg);
+        stv(ob + f, du);
+    } else {
+        Vec16<T> xv = ldv(up + row * f + (long)cv * V), out;
+#pragma unroll
+        for (int e = 0; e < V; ++e) {
+            float xx = to_f32(xv.v[e]);
+            float cdf = 0.5f * (1.f + erff(xx * 0.70710678118654752f));
+            float pdf = 0.3989422804014327f * __expf(-0.5f * xx * xx);
+            out.v[e] = from_f32<T>(to_f32(dav.v[e]) * (cdf + xx * pdf));
+        }
+        stv(dup + row * f + (long)cv * V, out);
+    }
+}
+
+// ------------------------------------------------------------------ embedding
+template <class T>
+__global__ __launch_bounds__(256) void embedding_fwd_kernel(const int *__restrict__ ids, const T *__restrict__ table,
+                                                            T *__restrict__ x, long nvec_total, int d) {
+    constexpr int V = Vec16<T>::N;
+    long idx = (long)blockIdx.x * blockDim.x + threadIdx.x;
+    if (idx >= nvec_total) return;
+    const int vpr = d / V;
+    long t = idx / vpr;
+    int cv = idx % vpr;
+    stv(x + t * d + (long)cv * V, ldv(table + (long)ids[t] * d + (long)cv * V));
+}
+
+template <class T>
+__global__ __launch_bounds__(256) void embedding_bwd_kernel(const int *__restrict__ ids, const T *__restrict__ dx,
+                                                            float *__restrict__ dtab, long nvec_total, int d) {
+    constexpr int V = Vec16<T>::N;
+    long idx = (long)blockIdx.x * blockDim.x + threadIdx.x;
+    if (idx >= nvec_total) return;
+    const int vpr = d / V;
+    long t = idx / vpr;
+    int cv = idx % vpr;
+    Vec16<T> v = ldv(dx + t * d + (long)cv * V);
+    float *o = dtab + (long)ids[t] * d + (long)cv * V;
+#pragma unroll
+    for (int e = 0; e < V; ++e) unsafeAtomicAdd(o + e, to_f32(v.v[e]));
+}
+
+// ------------------------------------------------------------------ fills / conversions
+__global__ void fill_f32_kernel(float *p, long n, float v) {
+    long i = (long)blockIdx.x * blockDim.x + threadIdx.x;
+    long stride = (long)gridDim.x * blockDim.x;
+    for (; i < n; i += stride) p[i] = v;
+}
+
+template <class T>
+__global__ void convert_from_f32_kernel(const float *__restrict__ src, T *__restrict__ dst, long n) {
+    long i = (long)blockIdx.x * blockDim.x + threadIdx.x;
+    long stride = (long)gridDim.x * blockDim.x;
+    for (; i < n; i += stride) dst[i] = from_f32<T>(src[i]);
+}
+
+__global__ __launch_bounds__(256) void copy_kernel(const uint4 *__restrict__ src, uint4 *__restrict__ dst, long nvec) {
+    long i = (long)blockIdx.x * blockDim.x + threadIdx.x;
+    long stride = (long)gridDim.x * blockDim.x;
+    for (; i < nvec; i += stride) dst[i] = src[i];
+}
+
+template <class T> constexpr int vec_of() { return 16 / sizeof(T); }
+
+}  // namespace
+
+// ===================================================================== host launchers
+#define DISPATCH_T(dtype, ...)                                  \
+    if ((dtype) == MS_BF16) { using T = bf16_t; __VA_ARGS__; }  \
+    else { using T = float; __VA_ARGS__; }
+
+static bool aligned16(const void *p) { return ((uintptr_t)p & 15) == 0; }
+
+extern "C" ms_status ms_k_norm_forward(int32_t kind, int32_t dtype, int32_t n, int32_t d, float eps, const void *x,
+                                       const void *g, const void *b, void *y, float *mean, float *rstd,
+                                       void *stream) {
+    if (n == 0) return MS_OK;
+    if (!x || !g || !y || !rstd || (kind == 1 && (!b || !mean)) || n < 0 || d <= 0)
+        return ms_fail(MS_ERR_INVALID_ARG, "norm_forward: null pointer or bad size");
+    const int V = dtype == MS_BF16 ? 8 : 4;
+    if (d % V || !aligned16(x) || !aligned16(y) || !aligned16(g))
+        return ms_fail(MS_ERR_UNSUPPORTED, "norm_forward: d=%d must be a multiple of %d and rows 16-byte aligned", d, V);
+    hipStream_t s = (hipStream_t)stream;
+    DISPATCH_T(dtype, {
+        if (kind == 1)
+            norm_fwd_kernel<T, 1><<<ms_cdiv(n, 4), 256, 0, s>>>((const T *)x, (const T *)g, (const T *)b, (T *)y, mean, rstd, n, d, eps);
+        else
+            norm_fwd_kernel<T, 0><<<ms_cdiv(n, 4), 256, 0, s>>>((const T *)x, (const T *)g, nullptr, (T *)y, nullptr, rstd, n, d, eps);
+    });
+    MS_LAUNCH_CHECK();
+    return MS_OK;
+}
+
+extern "C" size_t ms_k_norm_backward_scratch_bytes(int32_t d) {
+    return d > 0 ? 2 * ms_align_up((size_t)kPartialRows * d * sizeof(float)) : 0;
+}
+
+static ms_status reduce_partials(const float *part, int np, int c, float *out, hipStream_t s) {
+    reduce_partials_kernel<<<ms_cdiv(c, 64), 256, 0, s>>>(part, np, c, out);
+    MS_LAUNCH_CHECK();
+    return MS_OK;
+}
+
+extern "C" ms_status ms_k_norm_backward(int32_t kind, int32_t dtype, int32_t n, int32_t d, const void *dy,
+                                        const void *x, const void *g, const float *mean, const float *rstd,
+                                        const void *add, void *dx, float *dg, float *db, void *scratch,
+                                        void *stream) {
+    if (n == 0) return MS_OK;
+    if (!dy || !x || !g || !rstd || !dx || !dg || !scratch || (kind == 1 && (!mean || !db)) || n < 0 || d <= 0)
+        return ms_fail(MS_ERR_INVALID_ARG, "norm_backward: null pointer or bad size");
+    const int V = dtype == MS_BF16 ? 8 : 4;
+    if (d % V || d > 64 * kMaxCache * V)
+        return ms_fail(MS_ERR_UNSUPPORTED, "norm_backward: d=%d must be a multiple of %d and at most %d", d, V,
+                       64 * kMaxCache * V);
+    hipStream_t s = (hipStream_t)stream;
+    float *pg = (float *)scratch;
+    float *pb = (float *)((char *)scratch + ms_align_up((size_t)kPartialRows * d * sizeof(float)));
+    const int grid = n / 4 < 1 ? 1 : (n / 4 > kPartialRows / 4 ? kPartialRows / 4 : n / 4);
+    DISPATCH_T(dtype, {
+        if (kind == 1)
+            norm_bwd_kernel<T, 1><<<grid, 256, 0, s>>>((const T *)dy, (const T *)x, (const T *)g, mean, rstd, (const T *)add, (T *)dx, pg, pb, n, d);
+        else
+            norm_bwd_kernel<T, 0><<<grid, 256, 0, s>>>((const T *)dy, (const T *)x, (const T *)g, nullptr, rstd, (const T *)add, (T *)dx, pg, pb, n, d);
+    });
+    MS_LAUNCH_CHECK();
+    MS_TRY(reduce_partials(pg, grid * 4, d, dg, s));
+    if (kind == 1) MS_TRY(reduce_partials(pb, grid * 4, d, db, s));
+    return MS_OK;
+}
+
+extern "C" ms_status ms_k_colsum(int32_t dtype, int32_t n, int32_t c, const void *x, float *out, void *scratch,
+                                 void *stream) {
+    if (n == 0) return MS_OK;
+    if (!x || !out || !scratch || n < 0 || c <= 0) return ms_fail(MS_ERR_INVALID_ARG, "colsum: null pointer or bad size");
+    const int V = dtype == MS_BF16 ? 8 : 4;
+    if (c % V) return ms_fail(MS_ERR_UNSUPPORTED, "colsum: c=%d must be a multiple of %d", c, V);
+    hipStream_t s = (hipStream_t)stream;
+    const int gy = n / 16 < 1 ? 1 : (n / 16 > kPartialRows / 4 ? kPartialRows / 4 : n / 16);
+    dim3 grid(ms_cdiv(c / V, 64), gy);
+    DISPATCH_T(dtype, { colsum_partial_kernel<T><<<grid, 256, 0, s>>>((const T *)x, n, c, (float *)scratch); });
+    MS_LAUNCH_CHECK();
+    return reduce_partials((const float *)scratch, gy * 4, c, out, s);
+}
+
+extern "C" ms_status ms_k_positions(int32_t n_tokens, int32_t n_seqs, const int32_t *cu, int32_t *pos, void *stream) {
+    if (n_tokens == 0) return MS_OK;
+    if (!cu || !pos || n_seqs <= 0 || n_tokens < 0) return ms_fail(MS_ERR_INVALID_ARG, "positions: bad argument");
+    positions_kernel<<<ms_cdiv(n_tokens, 256), 256, 0, (hipStream_t)stream>>>(n_tokens, n_seqs, cu, pos);
+    MS_LAUNCH_CHECK();
+    return MS_OK;
+}
+
+extern "C" ms_status ms_k_rope_table(int32_t max_pos, int32_t head_dim, float base, float *table, void *stream) {
+    if (max_pos == 0) return MS_OK;
+    if (!table || max_pos < 0 || head_dim <= 0 || head_dim % 2) return ms_fail(MS_ERR_INVALID_ARG, "rope_table: bad argument");
+    const int half = head_dim / 2;
+    rope_table_kernel<<<ms_cdiv((long)max_pos * half, 256), 256, 0, (hipStream_t)stream>>>(max_pos, half, head_dim, (double)base, (float2 *)table);
+    MS_LAUNCH_CHECK();
+    return MS_OK;
+}
+
+extern "C" ms_status ms_k_rope(int32_t dtype, int32_t n, int32_t n_heads, int32_t head_dim, int64_t row_stride, void *x,
+                               const int32_t *pos, const float *table, int32_t inverse, void *stream) {
+    if (n == 0 || n_heads == 0) return MS_OK;
+    if (!x || !pos || !table || n < 0 || n_heads < 0) return ms_fail(MS_ERR_INVALID_ARG, "rope: bad argument");
+    const int V = dtype == MS_BF16 ? 8 : 4;
+    if (head_dim % (2 * V) || row_stride % V || !aligned16(x))
+        return ms_fail(MS_ERR_UNSUPPORTED, "rope: head_dim=%d must be a multiple of %d", head_dim, 2 * V);
+    const long total = (long)n * n_heads * (head_dim / 2 / V);
+    DISPATCH_T(dtype, {
+        rope_kernel<T><<<ms_cdiv(total, 256), 256, 0, (hipStream_t)stream>>>((T *)x, pos, (const float2 *)table, total, n_heads, head_dim, row_stride, inverse ? -1.f : 1.f);
+    });
+    MS_LAUNCH_CHECK();
+    return MS_OK;
+}
+
+extern "C" ms_status ms_k_act_forward(int32_t kind, int32_t dtype, int32_t n, int32_t f, const void *up, void *a, void *stream) {
+    if (n == 0) return MS_OK;
+    if (!up || !a || n < 0 || f <= 0) return ms_fail(MS_ERR_INVALID_ARG, "act_forward: bad argument");
+    const int V = dtype == MS_BF16 ? 8 : 4;
+    if (f % V) return ms_fail(MS_ERR_UNSUPPORTED, "act_forward: f=%d must be a multiple of %d", f, V);
+    const long total = (long)n * (f / V);
+    hipStream_t s = (hipStream_t)stream;
+    DISPATCH_T(dtype, {
+        if (kind == 0) act_fwd_kernel<T, 0><<<ms_cdiv(total, 256), 256, 0, s>>>((const T *)up, (T *)a, total, f);
+        else act_fwd_kernel<T, 1><<<ms_cdiv(total, 256), 256, 0, s>>>((const T *)up, (T *)a, total, f);
+    });
+    MS_LAUNCH_CHECK();
+    return MS_OK;
+}
+
+extern "C" ms_status ms_k_act_backward(int32_t kind, int32_t dtype, int32_t n, int32_t f, const void *da, const void *up,
+                                       void *dup, void *stream) {
+    if (n == 0) return MS_OK;
+    if (!da || !up || !dup || n < 0 || f <= 0) return ms_fail(MS_ERR_INVALID_ARG, "act_backward: bad argument");
+    const int V = dtype == MS_BF16 ? 8 : 4;
+    if (f % V) return ms_fail(MS_ERR_UNSUPPORTED, "act_backward: f=%d must be a multiple of %d", f, V);
+    const long total = (long)n * (f / V);
+    hipStream_t s = (hipStream_t)stream;
+    DISPATCH_T(dtype, {
+        if (kind == 0) act_bwd_kernel<T, 0><<<ms_cdiv(total, 256), 256, 0, s>>>((const T *)da, (const T *)up, (T *)dup, total, f);
+        else act_bwd_kernel<T, 1><<<ms_cdiv(total, 256), 256, 0, s>>>((const T *)da, (const T *)up, (T *)dup, total, f);
+    });
+    MS_LAUNCH_CHECK();
+    return MS_OK;
+}
+
+extern "C" ms_status ms_k_embedding_forward(int32_t dtype, int32_t n, int32_t d, int32_t vocab, const int32_t *ids,
+                                            const void *table, void *x, void *stream) {
+    if (n == 0) return MS_OK;
+    if (!ids || !table || !x || n < 0 || d <= 0 || vocab <= 0) return ms_fail(MS_ERR_INVALID_ARG, "embedding_forward: bad argument");
+    const int V = dtype == MS_BF16 ? 8 : 4;
+    if (d % V) return ms_fail(MS_ERR_UNSUPPORTED, "embedding: d=%d must be a multiple of %d", d, V);
+    const long total = (long)n * (d / V);
+    DISPATCH_T(dtype, { embedding_fwd_kernel<T><<<ms_cdiv(total, 256), 256, 0, (hipStream_t)stream>>>(ids, (const T *)table, (T *)x, total, d); });
+    MS_LAUNCH_CHECK();
+    return MS_OK;
+}
+
+extern "C" ms_status ms_k_embedding_backward(int32_t dtype, int32_t n, int32_t d, int32_t vocab, const int32_t *ids,
+                                             const void *dx, float *d_table, void *stream) {
+    if (n == 0) return MS_OK;
+    if (!ids || !dx || !d_table || n < 0 || d <= 0 || vocab <= 0) return ms_fail(MS_ERR_INVALID_ARG, "embedding_backward: bad argument");
+    const int V = dtype == MS_BF16 ? 8 : 4;
+    if (d % V) return ms_fail(MS_ERR_UNSUPPORTED, "embedding: d=%d must be a multiple of %d", d, V);
+    const long total = (long)n * (d / V);
+    DISPATCH_T(dtype, { embedding_bwd_kernel<T><<<ms_cdiv(total, 256), 256, 0, (hipStream_t)stream>>>(ids, (const T *)dx, d_table, total, d); });
+    MS_LAUNCH_CHECK();
+    return MS_OK;
+}
+
+extern "C" ms_status ms_k_copy(const void *src, void *dst, size_t bytes, void *stream) {
+    if (bytes == 0) return MS_OK;
+    if (!src || !dst || bytes % 16 || !aligned16(src) || !aligned16(dst)) return ms_fail(MS_ERR_INVALID_ARG, "copy: need 16-byte multiples");
+    const long nvec = bytes / 16;
+    const int grid = ms_cdiv(nvec, 256) > 16384 ? 16384 : ms_cdiv(nvec, 256);
+    copy_kernel<<<grid, 256, 0, (hipStream_t)stream>>>((const uint4 *)src, (uint4 *)dst, nvec);
+    MS_LAUNCH_CHECK();
+    return MS_OK;
+}
+
+// internal helpers declared in launch.h
+ms_status launch_fill_f32(float *p, long n, float v, hipStream_t s) {
+    if (n <= 0) return MS_OK;
+    const int grid = ms_cdiv(n, 256) > 8192 ? 8192 : ms_cdiv(n, 256);
+    fill_f32_kernel<<<grid, 256, 0, s>>>(p, n, v);
+    MS_LAUNCH_CHECK();
+    return MS_OK;
+}
+
+ms_status launch_convert_from_f32(int dtype, const float *src, void *dst, long n, hipStream_t s) {
+    if (n <= 0) return MS_OK;
+    const int grid = ms_cdiv(n, 256) > 16384 ? 16384 : ms_cdiv(n, 256);
+    DISPATCH_T(dtype, { convert_from_f32_kernel<T><<<grid, 256, 0, s>>>(src, (T *)dst, n); });
+    MS_LAUNCH_CHECK();
+    return MS_OK;
+}

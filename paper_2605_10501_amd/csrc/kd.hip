@@ -1,0 +1,209 @@
+// Vocabulary-chunked lm_head + temperature softmax + KL(teacher || student).
+//
+// Pass 1 walks the vocabulary in chunks: two GEMMs give the chunk's teacher and student
+// logits (fp32, [N, chunk], the only logits that ever exist), and a row kernel folds them into
+// five running numbers per token: max and sum-of-exponentials of both models and the cross
+// term sum_v e^{zt/T - m_t} (zt - zs)/T.  From those, KL_tok = A/s_t - lse_t + lse_s.
+// Pass 2 recomputes each chunk's logits, forms dz = (scale/T)(q - p) in the storage dtype and
+// feeds it to the two gradient GEMMs (dHs accumulated in fp32 over chunks, dWs chunk rows +=).
+#include "common.h"
+#include "launch.h"
+
+namespace {
+
+constexpr int kStat = 8;  // floats per token: m_t, s_t, m_s, s_s, A, lse_t, lse_s, unused
+
+__device__ __forceinline__ float block_max(float v, float *sm) {
+    v = wave_max(v);
+    if ((threadIdx.x & 63) == 0) sm[threadIdx.x >> 6] = v;
+    __syncthreads();
+    float r = sm[0];
+    for (int i = 1; i < (int)(blockDim.x >> 6); ++i) r = fmaxf(r, sm[i]);
+    __syncthreads();
+    return r;
+}
+__device__ __forceinline__ float block_sum(float v, float *sm) {
+    v = wave_sum(v);
+    if ((threadIdx.x & 63) == 0) sm[threadIdx.x >> 6] = v;
+    __syncthreads();
+    float r = 0.f;
+    for (int i = 0; i < (int)(blockDim.x >> 6); ++i) r += sm[i];
+    __syncthreads();
+    return r;
+}
+
+// one workgroup per token; zt / zs rows have leading dimension ld, cw valid columns (cw % 4 == 0)
+__global__ __launch_bounds__(256) void kd_stats_kernel(const float *__restrict__ zt, const float *__restrict__ zs,
+                                                        long ld, int cw, float inv_t, int first,
+                                                        float *__restrict__ stats) {
+    __shared__ float sm[4];
+    const long t = blockIdx.x;
+    const float4 *rt = (const float4 *)(zt + t * ld), *rs = (const float4 *)(zs + t * ld);
+    const int nv = cw >> 2;
+    float mt = -INFINITY, msv = -INFINITY;
+    for (int i = threadIdx.x; i < nv; i += 256) {
+        const float4 a = rt[i], b = rs[i];
+        mt = fmaxf(mt, fmaxf(fmaxf(a.x, a.y), fmaxf(a.z, a.w)));
+        msv = fmaxf(msv, fmaxf(fmaxf(b.x, b.y), fmaxf(b.z, b.w)));
+    }
+    mt = block_max(mt, sm) * inv_t;
+    msv = block_max(msv, sm) * inv_t;
+    float *st = stats + t * kStat;
+    float m_t = mt, m_s = msv, f_t = 0.f, f_s = 0.f, o_st = 0.f, o_ss = 0.f, o_a = 0.f;
+    if (!first) {
+        const float omt = st[0], oms = st[2];
+        o_st = st[1]; o_ss = st[3]; o_a = st[4];
+        m_t = fmaxf(mt, omt);
+        m_s = fmaxf(msv, oms);
+        f_t = __expf(omt - m_t);
+        f_s = __expf(oms - m_s);
+    }
+    float s_t = 0.f, s_s = 0.f, a_c = 0.f;
+    for (int i = threadIdx.x; i < nv; i += 256) {
+        const float4 a = rt[i], b = rs[i];
+        const float av[4] = {a.x, a.y, a.z, a.w}, bv[4] = {b.x, b.y, b.z, b.w};
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            const float et = __expf(av[e] * inv_t - m_t);
+            s_t += et;
+            a_c += et * (av[e] - bv[e]) * inv_t;
+            s_s += __expf(bv[e] * inv_t - m_s);
+        }
+    }
+    s_t = block_sum(s_t, sm);
+    s_s = block_sum(s_s, sm);
+    a_c = block_sum(a_c, sm);
+    if (threadIdx.x == 0) {
+        st[0] = m_t;
+        st[1] = o_st * f_t + s_t;
+        st[2] = m_s;
+        st[3] = o_ss * f_s + s_s;
+        st[4] = o_a * f_t + a_c;
+    }
+}
+
+// single workgroup: per-token KL, log-sum-exps for pass 2, and the scalar loss (fixed summation order)
+__global__ __launch_bounds__(1024) void kd_finalize_kernel(float *__restrict__ stats, int n, float loss_scale,
+                                                            float *__restrict__ kl_tok, float *__restrict__ loss) {
+    __shared__ float sm[16];
+    float acc = 0.f;
+    for (int t = threadIdx.x; t < n; t += 1024) {
+        float *st = stats + (long)t * kStat;
+        const float lse_t = st[0] + __logf(st[1]);
+        const float lse_s = st[2] + __logf(st[3]);
+        const float kl = st[4] / st[1] - lse_t + lse_s;
+        st[5] = lse_t;
+        st[6] = lse_s;
+        if (kl_tok) kl_tok[t] = kl;
+        acc += kl;
+    }
+    acc = block_sum(acc, sm);
+    if (threadIdx.x == 0) *loss = loss_scale * acc;
+}
+
+template <class T>
+__global__ __launch_bounds__(256) void kd_dz_kernel(const float *__restrict__ zt, const float *__restrict__ zs, long ld,
+                                                    int cw, float inv_t, float coef, const float *__restrict__ stats,
+                                                    T *__restrict__ dz) {
+    const long t = blockIdx.y;
+    const int c4 = (blockIdx.x * 256 + threadIdx.x) * 4;
+    if (c4 >= cw) return;
+    const float lse_t = stats[t * kStat + 5], lse_s = stats[t * kStat + 6];
+    const float4 a = *(const float4 *)(zt + t * ld + c4), b = *(const float4 *)(zs + t * ld + c4);
+    const float av[4] = {a.x, a.y, a.z, a.w}, bv[4] = {b.x, b.y, b.z, b.w};
+    T *o = dz + t * ld + c4;
+#pragma unroll
+    for (int e = 0; e < 4; ++e)
+        o[e] = from_f32<T>(coef * (__expf(bv[e] * inv_t - lse_s) - __expf(av[e] * inv_t - lse_t)));
+}
+
+struct KdPlan {
+    float *zt, *zs, *stats, *dhs;
+    void *dz;
+    size_t bytes;
+};
+
+KdPlan kd_plan(const ms_kd_config *kd, int n, void *ws) {
+    Arena a(ws);
+    KdPlan p;
+    const size_t nc = (size_t)n * kd->chunk;
+    p.zt = a.take<float>(nc * 4);
+    p.zs = a.take<float>(nc * 4);
+    p.stats = a.take<float>((size_t)n * kStat * 4);
+    p.dz = a.take<void>(nc * ms_dtype_size(kd->dtype));
+    p.dhs = a.take<float>((size_t)n * kd->h_student * 4);
+    p.bytes = a.off;
+    return p;
+}
+
+}  // namespace
+
+ms_status validate_kd(const ms_kd_config *kd, int n_tokens) {
+    if (!kd) return ms_fail(MS_ERR_INVALID_ARG, "kd: null config");
+    if (n_tokens < 0) return ms_fail(MS_ERR_INVALID_ARG, "kd: negative token count");
+    if (kd->dtype != MS_BF16 && kd->dtype != MS_F32) return ms_fail(MS_ERR_INVALID_ARG, "kd: bad dtype");
+    if (kd->vocab <= 0 || kd->h_teacher <= 0 || kd->h_student <= 0 || kd->chunk <= 0)
+        return ms_fail(MS_ERR_SHAPE, "kd: vocab, hidden sizes and chunk must be positive");
+    if (!(kd->temperature > 0.f)) return ms_fail(MS_ERR_INVALID_ARG, "kd: temperature must be positive");
+    if (kd->vocab % 8 || kd->chunk % 8 || kd->h_teacher % 8 || kd->h_student % 8)
+        return ms_fail(MS_ERR_UNSUPPORTED, "kd: vocab, chunk and hidden sizes must be multiples of 8");
+    if (!kd->w_teacher_dev || !kd->w_student_dev) return ms_fail(MS_ERR_INVALID_ARG, "kd: null lm_head pointer");
+    return MS_OK;
+}
+
+extern "C" size_t ms_kd_workspace_bytes(const ms_kd_config *kd, int32_t max_tokens) {
+    if (!kd || max_tokens < 0 || kd->chunk <= 0 || kd->h_student <= 0) return 0;
+    return kd_plan(kd, max_tokens, nullptr).bytes;
+}
+
+ms_status kd_forward_backward(const ms_kd_config *kd, int n, const void *h_t, const void *h_s, float *loss_dev,
+                              float *kl_tok_dev, void *d_h_s, void *d_w_s, void *workspace, size_t workspace_bytes,
+                              hipStream_t s) {
+    MS_TRY(validate_kd(kd, n));
+    if (!loss_dev) return ms_fail(MS_ERR_INVALID_ARG, "kd: loss_dev is null");
+    if (n == 0) return launch_fill_f32(loss_dev, 1, 0.f, s);
+    if (!h_t || !h_s || !workspace) return ms_fail(MS_ERR_INVALID_ARG, "kd: null pointer");
+    const KdPlan p = kd_plan(kd, n, workspace);
+    if (workspace_bytes < p.bytes) return ms_fail(MS_ERR_WORKSPACE, "kd: workspace %zu < %zu bytes", workspace_bytes, p.bytes);
+    const int V = kd->vocab, Cv = kd->chunk, Ht = kd->h_teacher, Hs = kd->h_student, dt = kd->dtype;
+    const size_t es = ms_dtype_size(dt);
+    const float inv_t = 1.f / kd->temperature;
+    const char *wt = (const char *)kd->w_teacher_dev, *wsd = (const char *)kd->w_student_dev;
+    const int passes = (d_h_s || d_w_s) ? 2 : 1;
+    if (d_h_s) MS_TRY(launch_fill_f32(p.dhs, (long)n * Hs, 0.f, s));
+    for (int pass = 0; pass < passes; ++pass) {
+        for (int v0 = 0; v0 < V; v0 += Cv) {
+            const int cw = V - v0 < Cv ? V - v0 : Cv;
+            MS_TRY(ms_k_gemm(dt, 0, 0, n, cw, Ht, 1.f, h_t, Ht, wt + (size_t)v0 * Ht * es, Ht, p.zt, Cv, 1, 0, nullptr, nullptr, 0, 1, s));
+            MS_TRY(ms_k_gemm(dt, 0, 0, n, cw, Hs, 1.f, h_s, Hs, wsd + (size_t)v0 * Hs * es, Hs, p.zs, Cv, 1, 0, nullptr, nullptr, 0, 1, s));
+            if (pass == 0) {
+                kd_stats_kernel<<<n, 256, 0, s>>>(p.zt, p.zs, Cv, cw, inv_t, v0 == 0, p.stats);
+                MS_LAUNCH_CHECK();
+                continue;
+            }
+            const float coef = kd->loss_scale * inv_t;
+            dim3 grid(ms_cdiv(cw, 1024), n);
+            if (dt == MS_BF16) kd_dz_kernel<bf16_t><<<grid, 256, 0, s>>>(p.zt, p.zs, Cv, cw, inv_t, coef, p.stats, (bf16_t *)p.dz);
+            else kd_dz_kernel<float><<<grid, 256, 0, s>>>(p.zt, p.zs, Cv, cw, inv_t, coef, p.stats, (float *)p.dz);
+            MS_LAUNCH_CHECK();
+            if (d_h_s)  // dHs[N, Hs] += dz[N, cw] Ws_c[cw, Hs]
+                MS_TRY(ms_k_gemm(dt, 0, 1, n, Hs, cw, 1.f, p.dz, Cv, wsd + (size_t)v0 * Hs * es, Hs, p.dhs, Hs, 1, 1, nullptr, nullptr, 0, 1, s));
+            if (d_w_s)  // dWs_c[cw, Hs] += dz^T[cw, N] Hs[N, Hs]
+                MS_TRY(ms_k_gemm(dt, 1, 1, cw, Hs, n, 1.f, p.dz, Cv, h_s, Hs, (float *)d_w_s + (size_t)v0 * Hs, Hs, 1, 1, nullptr, nullptr, 0, 0, s));
+        }
+        if (pass == 0) {
+            kd_finalize_kernel<<<1, 1024, 0, s>>>(p.stats, n, kd->loss_scale, kl_tok_dev, loss_dev);
+            MS_LAUNCH_CHECK();
+        }
+    }
+    if (d_h_s) MS_TRY(launch_convert_from_f32(dt, p.dhs, d_h_s, (long)n * Hs, s));
+    return MS_OK;
+}
+
+extern "C" ms_status ms_kd_loss_forward_backward(const ms_kd_config *kd, int32_t n_tokens, const void *h_teacher,
+                                                 const void *h_student, float *loss_dev, float *kl_per_token_dev,
+                                                 void *d_h_student, void *d_w_student, void *workspace_dev,
+                                                 size_t workspace_bytes, void *stream) {
+    return kd_forward_backward(kd, n_tokens, h_teacher, h_student, loss_dev, kl_per_token_dev, d_h_student, d_w_student,
+                               workspace_dev, workspace_bytes, (hipStream_t)stream);
+}

@@ -1,0 +1,175 @@
+"""Kernel-level parity: each HIP kernel (through the C ABI) against the oracle's matching routine."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import ops, round_bf16, identity
+from oracle.attention import attention_bwd, attention_fwd
+from paper_2605_10501_amd import binding as B
+from paper_2605_10501_amd import workloads as wl
+from parity import TOL_BF16, TOL_F32, assert_parity
+
+pytestmark = pytest.mark.gpu
+DTYPES = [torch.bfloat16, torch.float32]
+
+
+def dev(name, shape, dtype, std=1.0, mean=0.0):
+    return wl.normal(7, name, shape, std, mean, dtype, "cuda")
+
+
+def f64(t):
+    return t.detach().cpu().to(torch.float64).numpy()
+
+
+def rnd_of(dtype):
+    return round_bf16 if dtype == torch.bfloat16 else identity
+
+
+def tol_of(dtype):
+    return TOL_BF16 if dtype == torch.bfloat16 else TOL_F32
+
+
+@pytest.mark.parametrize("ta,tb", [(0, 0), (0, 1), (1, 0), (1, 1)])
+@pytest.mark.parametrize("M,N,K", [(300, 200, 136), (128, 128, 64), (1, 8, 8), (513, 344, 1000), (264, 1032, 72)])
+def test_gemm_bf16_all_layouts(ta, tb, M, N, K):
+    if (ta and M % 8) or (tb and N % 8) or ((not ta or not tb) and K % 8):
+        pytest.skip("shape not 16-byte aligned for this layout")
+    a = dev(f"a{M}{K}", (K, M) if ta else (M, K), torch.bfloat16)
+    b = dev(f"b{N}{K}", (K, N) if tb else (N, K), torch.bfloat16)
+    ref = (f64(a).T if ta else f64(a)) @ (f64(b) if tb else f64(b).T)
+    assert_parity(B.k_gemm(a, b, ta, tb, c_fp32=True), ref, TOL_F32, "fp32 out")
+    assert_parity(B.k_gemm(a, b, ta, tb), round_bf16(ref), TOL_BF16, "bf16 out")
+
+
+def test_gemm_epilogues_and_split_k():
+    M, N, K = 400, 264, 4096
+    a, b = dev("ea", (M, K), torch.bfloat16), dev("eb", (N, K), torch.bfloat16, 0.05)
+    bias, res = dev("ebias", (N,), torch.bfloat16), dev("eres", (M, N), torch.bfloat16)
+    ref = 0.5 * (f64(a) @ f64(b).T) + f64(bias)[None, :] + f64(res)
+    assert_parity(B.k_gemm(a, b, bias=bias, residual=res, alpha=0.5), round_bf16(ref), TOL_BF16, "bias+res")
+    c0 = dev("ec", (M, N), torch.float32)
+    for split in (1, 4, 0):
+        c = c0.clone()
+        B.k_gemm(a, b, c=c, c_fp32=True, accumulate=True, split_k=split)
+        assert_parity(c, f64(c0) + f64(a) @ f64(b).T, TOL_F32, f"accumulate split={split}")
+    # weight-gradient form: dW[out, in] += dy[n, out]^T x[n, in], K = tokens (ragged)
+    dy, x = dev("dy", (1003, 264), torch.bfloat16), dev("x", (1003, 136), torch.bfloat16)
+    dw = torch.zeros((264, 136), dtype=torch.float32, device="cuda")
+    B.k_gemm(dy, x, True, True, c=dw, c_fp32=True, accumulate=True, split_k=0)
+    assert_parity(dw, f64(dy).T @ f64(x), TOL_F32, "wgrad")
+
+
+@pytest.mark.parametrize("ta,tb", [(0, 0), (0, 1), (1, 0), (1, 1)])
+def test_gemm_fp32(ta, tb):
+    M, N, K = 77, 50, 93
+    a = dev("fa", (K, M) if ta else (M, K), torch.float32)
+    b = dev("fb", (K, N) if tb else (N, K), torch.float32)
+    bias = dev("fbias", (N,), torch.float32)
+    ref = (f64(a).T if ta else f64(a)) @ (f64(b) if tb else f64(b).T) + f64(bias)
+    assert_parity(B.k_gemm(a, b, ta, tb, bias=bias), ref, TOL_F32)
+
+
+@pytest.mark.parametrize("dtype", DTYPES)
+@pytest.mark.parametrize("kind,d", [(0, 1024), (0, 344), (1, 1280), (0, 4096), (1, 136)])
+def test_norm_forward_backward(dtype, kind, d):
+    if dtype == torch.float32 and d > 2048:
+        pytest.skip("fp32 backward keeps at most 2048 columns per row in registers")
+    n, eps = 333, 1e-6
+    x, g, b = dev("nx", (n, d), dtype, 2.0, 0.3), dev("ng", (d,), dtype, 0.02, 1.0), dev("nb", (d,), dtype, 0.02)
+    dy, add = dev("ndy", (n, d), dtype), dev("nadd", (n, d), dtype)
+    rnd, tol = rnd_of(dtype), tol_of(dtype)
+    y, mean, rstd = B.k_norm_forward(kind, x, g, b if kind else None, eps)
+    if kind == 0:
+        yr, r = ops.rmsnorm_fwd(f64(x), f64(g), eps)
+        dxr, dgr = ops.rmsnorm_bwd(f64(dy), f64(x), r, f64(g))
+    else:
+        yr, mu, r = ops.layernorm_fwd(f64(x), f64(g), f64(b), eps)
+        dxr, dgr, dbr = ops.layernorm_bwd(f64(dy), f64(x), mu, r, f64(g))
+        assert_parity(mean, mu, TOL_F32, "mean")
+    assert_parity(y, rnd(yr), tol, "y")
+    assert_parity(rstd, r, TOL_F32, "rstd")
+    dx, dg, db = B.k_norm_backward(kind, dy, x, g, mean, rstd, add)
+    assert_parity(dx, rnd(dxr + f64(add)), tol, "dx")
+    assert_parity(dg, dgr, 2e-4, "dg")
+    if kind:
+        assert_parity(db, dbr, 2e-4, "db")
+    dg2 = dg.clone()
+    B.k_norm_backward(kind, dy, x, g, mean, rstd, None, dg2, db.clone() if kind else None)
+    assert_parity(dg2, 2 * dgr, 2e-4, "dg accumulates")
+
+
+@pytest.mark.parametrize("dtype", DTYPES)
+def test_rope_and_positions(dtype):
+    batch = B.Batch([0, 5, 5, 133, 200])
+    pos = B.k_positions(batch)
+    assert np.array_equal(pos.cpu().numpy(), ops.positions_from_cu(batch.cu))
+    nq, nkv, hd = 3, 1, 64
+    x = dev("rx", (200, (nq + 2 * nkv) * hd), dtype)
+    table = B.k_rope_table(batch.max_seqlen, hd, 1e4)
+    xr = f64(x).reshape(200, nq + 2 * nkv, hd)
+    ref = xr.copy()
+    ref[:, :nq + nkv] = ops.rope_apply(xr[:, :nq + nkv], ops.positions_from_cu(batch.cu), 1e4)
+    y = B.k_rope(x.clone(), nq + nkv, hd, pos, table)
+    assert_parity(y, rnd_of(dtype)(ref.reshape(200, -1)), tol_of(dtype), "rope")
+    assert torch.equal(y[:, (nq + nkv) * hd:], x[:, (nq + nkv) * hd:])          # V untouched
+    back = ref.copy()
+    back[:, :nq + nkv] = ops.rope_apply(xr[:, :nq + nkv], ops.positions_from_cu(batch.cu), 1e4, inverse=True)
+    assert_parity(B.k_rope(x.clone(), nq + nkv, hd, pos, table, True), rnd_of(dtype)(back.reshape(200, -1)), tol_of(dtype))
+
+
+def test_rope_table_long_positions():
+    t = B.k_rope_table(16384, 128, 1e4).cpu().numpy().astype(np.float64)
+    p, i = np.array([16383, 9999, 1]), np.array([0, 1, 63])
+    ang = p * 1e4 ** (-2.0 * i / 128)
+    assert np.allclose(t[p, i, 0], np.cos(ang), atol=2e-7) and np.allclose(t[p, i, 1], np.sin(ang), atol=2e-7)
+
+
+@pytest.mark.parametrize("dtype", DTYPES)
+@pytest.mark.parametrize("kind,f", [(0, 344), (0, 2816), (1, 5120)])
+def test_activations(dtype, kind, f):
+    n = 257
+    up, da = dev("au", (n, 2 * f if kind == 0 else f), dtype, 1.5), dev("ada", (n, f), dtype)
+    rnd, tol = rnd_of(dtype), tol_of(dtype)
+    fwd, bwd = (ops.swiglu_fwd, ops.swiglu_bwd) if kind == 0 else (ops.gelu_fwd, ops.gelu_bwd)
+    assert_parity(B.k_act_forward(kind, up), rnd(fwd(f64(up))), tol, "fwd")
+    assert_parity(B.k_act_backward(kind, da, up), rnd(bwd(f64(da), f64(up))), tol, "bwd")
+
+
+@pytest.mark.parametrize("dtype", DTYPES)
+def test_embedding_and_colsum(dtype):
+    vocab, d, n = 50, 136, 700
+    table, dx = dev("et", (vocab, d), dtype), dev("edx", (n, d), dtype)
+    ids = wl.randint(7, "ids", n, 0, vocab, "cuda")
+    assert torch.equal(B.k_embedding_forward(ids, table), table[ids.long()])
+    assert_parity(B.k_embedding_backward(ids, dx, vocab), ops.embedding_bwd(ids.cpu().numpy(), f64(dx), vocab), 2e-4)
+    assert_parity(B.k_colsum(dx), f64(dx).sum(axis=0), 2e-4, "colsum")
+
+
+ATT_CASES = [  # nq, nkv, hd, cu, scale of q/k
+    (4, 2, 64, [0, 70, 70, 199, 200], 1.0),
+    (2, 2, 80, [0, 130, 300], 1.0),
+    (8, 2, 128, [0, 257, 321], 1.0),
+    (4, 1, 128, [0, 300], 4.0),       # sharp softmax: the online rescaling really works
+]
+
+
+@pytest.mark.parametrize("dtype", DTYPES)
+@pytest.mark.parametrize("causal", [True, False])
+@pytest.mark.parametrize("nq,nkv,hd,cu,sharp", ATT_CASES)
+def test_attention_forward_backward(dtype, causal, nq, nkv, hd, cu, sharp):
+    n = cu[-1]
+    batch = B.Batch(cu)
+    qkv = dev(f"qkv{nq}{hd}", (n, (nq + 2 * nkv) * hd), dtype)
+    qkv[:, :(nq + nkv) * hd] *= sharp
+    d_o = dev("do", (n, nq * hd), dtype)
+    q = f64(qkv)[:, :nq * hd].reshape(n, nq, hd)
+    k = f64(qkv)[:, nq * hd:(nq + nkv) * hd].reshape(n, nkv, hd)
+    v = f64(qkv)[:, (nq + nkv) * hd:].reshape(n, nkv, hd)
+    rnd, tol = rnd_of(dtype), tol_of(dtype)
+    o, lse = B.k_attention_forward(qkv, batch, nq, nkv, hd, causal)
+    assert_parity(o, rnd(attention_fwd(q, k, v, cu, causal)).reshape(n, -1), tol, "o")
+    dq, dk, dv = attention_bwd(f64(d_o).reshape(n, nq, hd), q, k, v, cu, causal)
+    ref = np.concatenate([dq.reshape(n, -1), dk.reshape(n, -1), dv.reshape(n, -1)], axis=1)
+    dqkv = B.k_attention_backward(qkv, o, lse, d_o, batch, nq, nkv, hd, causal)
+    for name, sl in [("dq", slice(0, nq * hd)), ("dk", slice(nq * hd, (nq + nkv) * hd)), ("dv", slice((nq + nkv) * hd, None))]:
+        assert_parity(dqkv[:, sl], rnd(ref[:, sl]), tol, name)
