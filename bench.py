@@ -1,0 +1,182 @@
+#!/usr/bin/env python3
+"""One-GPU benchmark of the section hot path on the mid-size distillation workload (c2).
+
+A step = one packed micro-batch of 16384 tokens through the whole path: teacher section forward
+(8 layers), student section forward + KD loss + backward (4 layers).  Prints ONE JSON line:
+whole-step tokens/s, the roofline of the dominant kernel (bf16 MFMA GEMM) from per-launch HIP
+events recorded by the library, and the CPU oracle timed on a bounded sample of the same workload.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA
+PEAK_HBM_GBS = 8000.0       # MI355X HBM3E
+
+
+def model_flops(work):
+    """Algorithmic flops of one step: GEMMs 2*M*N*K, causal attention over unmasked pairs only,
+    backward = 2x GEMM forward and 2.5x attention forward, KD without the pass-2 recompute."""
+    n = work.n_tokens
+    pairs = sum(l * (l + 1) // 2 for l in work.lengths if l)
+
+    def section(cfg, bwd):
+        gemm = 2.0 * cfg.layer_params() * n * cfg.n_layers
+        attn = 4.0 * cfg.n_q_heads * cfg.head_dim * pairs * cfg.n_layers
+        return (gemm * 3 + attn * 3.5) if bwd else (gemm + attn)
+
+    kd = work.kd
+    return dict(teacher=section(work.teacher, False), student=section(work.student, True),
+                kd=2.0 * n * kd.vocab * (kd.h_teacher + kd.h_student) + 4.0 * n * kd.vocab * kd.h_student)
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="c2")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-sample-tokens", type=int, default=384)
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py measures one GPU's section compute; this build has no multi-GPU path (run with --gpus 1)",
+              file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from paper_2605_10501_amd import binding as B
+    from paper_2605_10501_amd import workloads as wl
+
+    if not torch.cuda.is_available():
+        print("bench.py needs a GPU", file=sys.stderr)
+        sys.exit(2)
+    B.lib()
+    dev = "cuda"
+    work = wl.workload(args.workload, 0)
+    t_cfg, s_cfg, kd = work.teacher, work.student, work.kd
+    dt = t_cfg.torch_dtype
+    tw, sw = wl.section_weights(t_cfg, 0, "teacher", dev), wl.section_weights(s_cfg, 0, "student", dev)
+    wt = wl.normal(0, "lm_head.t", (kd.vocab, kd.h_teacher), 0.02, 0.0, dt, dev)
+    ws = wl.normal(0, "lm_head.s", (kd.vocab, kd.h_student), 0.02, 0.0, dt, dev)
+    cu = wl.cu_seqlens_of(work.lengths)
+    n = cu[-1]
+    ids = wl.randint(0, "ids", n, 0, t_cfg.vocab, dev)
+    batch = B.Batch(cu)
+    grads = B.zero_grads(sw)
+    d_ws = torch.zeros((kd.vocab, kd.h_student), dtype=torch.float32, device=dev)
+    ws_t = B.workspace(B.section_workspace_bytes(t_cfg, n, batch.max_seqlen, False), dev, "teacher")
+    ws_s = B.workspace(B.section_workspace_bytes(s_cfg, n, batch.max_seqlen, True) + B.kd_workspace_bytes(kd, n), dev, "student")
+    h_t = torch.empty((n, t_cfg.d_model), dtype=dt, device=dev)
+
+    def teacher():
+        return B.section_forward(t_cfg, tw, batch, ids, h_out=h_t, ws=ws_t)
+
+    def student():
+        return B.section_forward_backward(s_cfg, sw, grads, batch, ids, kd=kd, w_teacher=wt, w_student=ws,
+                                          h_teacher=h_t, d_w_student=d_ws, ws=ws_s)
+
+    def step():
+        teacher()
+        return student()
+
+    def timed(fn, k):
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(k):
+            out = fn()
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) / k, out
+
+    for _ in range(args.warmup):
+        step()
+    sec_step, out = timed(step, args.steps)
+    loss = float(out["loss"].item())
+    sec_teacher, _ = timed(teacher, args.steps)
+    sec_student, _ = timed(student, args.steps)
+
+    # per-kernel durations from HIP events on the launch stream (separate, untimed-for-value steps)
+    B.profile_enable(1)
+    prof_steps = min(args.steps, 3)
+    for _ in range(prof_steps):
+        step()
+    torch.cuda.synchronize()
+    prof = B.profile_read()
+    B.profile_enable(0)
+    fl = model_flops(work)
+    g_n, g_ms, g_work = prof["gemm_nt"]
+    gt_n, gt_ms, gt_work = prof["gemm_t"]
+    achieved = g_work / (g_ms * 1e-3) / 1e12 if g_ms > 0 else 0.0
+    kernels = {}
+    for name, (cnt, ms, workv) in prof.items():
+        if cnt:
+            kernels[name] = {"launches_per_step": cnt / prof_steps, "ms_per_step": ms / prof_steps,
+                             "avg_us": 1e3 * ms / cnt}
+            if workv > 0:
+                unit = "TFLOP/s" if name.startswith("gemm") else "GB/s"
+                kernels[name][unit] = workv / (ms * 1e-3) / (1e12 if unit == "TFLOP/s" else 1e9)
+    total_flops = fl["teacher"] + fl["student"] + fl["kd"]
+    result = {
+        "metric": "KD step tokens/s (teacher fwd + student fwd+bwd + fused KL loss), 1 GPU",
+        "value": n / sec_step, "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": 1e3 * sec_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": f"{work.name}: mid-size KD step, {n} packed tokens, {batch.n_seqs} sequences "
+                               f"(max {batch.max_seqlen}), teacher 8L d2048 16/4 heads F5504, student 4L d1024 8/2 "
+                               f"heads F2816, vocab 32000, T=2, chunk {kd.chunk}"},
+        "teacher_fwd_tokens_per_s": n / sec_teacher, "student_fwd_bwd_kd_tokens_per_s": n / sec_student,
+        "model_tflop_per_step": total_flops / 1e12,
+        "mfma_frac_whole_step": total_flops / sec_step / 1e12 / PEAK_BF16_TFLOPS,
+        "mfma_frac_teacher_fwd": fl["teacher"] / sec_teacher / 1e12 / PEAK_BF16_TFLOPS,
+        "mfma_frac_student_fwd_bwd_kd": (fl["student"] + fl["kd"]) / sec_student / 1e12 / PEAK_BF16_TFLOPS,
+        "loss": loss, "logits_to_hidden_ratio": kd.vocab / kd.h_teacher,
+        "roofline": {"kernel": "gemm_bf16_kernel (A[M,K] B[N,K]^T, all forward linears and lm_head chunks)",
+                     "bound": "mfma", "achieved": achieved, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
+                     "frac": achieved / PEAK_BF16_TFLOPS, "traffic": None,
+                     "launches_per_step": g_n / prof_steps, "avg_launch_us": 1e3 * g_ms / max(g_n, 1),
+                     "flops_per_launch_avg": g_work / max(g_n, 1)},
+        "kernels": kernels,
+    }
+    if not args.no_cpu_baseline:
+        result["cpu_baseline"] = cpu_baseline(work, tw, sw, wt, ws, ids, args.cpu_sample_tokens)
+    print(json.dumps(result))
+
+
+def cpu_baseline(work, tw, sw, wt, ws, ids, sample_tokens):
+    """The oracle as it stands, timed on the first `sample_tokens` tokens of the same batch
+    (sequences truncated to fit), all host threads numpy's BLAS uses."""
+    import numpy as np
+    from threadpoolctl import threadpool_info
+    from oracle import round_bf16
+    from oracle.section import SectionSpec
+    from oracle.step import distill_step
+    from paper_2605_10501_amd import workloads as wl
+
+    def spec(c):
+        return SectionSpec(c.arch, c.n_layers, c.d_model, c.n_q_heads, c.n_kv_heads, c.head_dim, c.d_ffn, c.vocab,
+                           c.norm_eps, c.rope_base)
+    lens, tot = [], 0
+    for l in work.lengths:
+        if l and tot < sample_tokens:
+            lens.append(min(l, sample_tokens - tot))
+            tot += lens[-1]
+    cu = wl.cu_seqlens_of(lens)
+    t_w, s_w, w_t, w_s = wl.to_f64(tw), wl.to_f64(sw), wl.to_f64(wt), wl.to_f64(ws)
+    ids_h = ids[:tot].cpu().numpy()
+    t0 = time.perf_counter()
+    out = distill_step(spec(work.teacher), t_w, spec(work.student), s_w, cu, ids_h, w_t, w_s,
+                       work.kd.temperature, 1.0 / tot, round_bf16)
+    sec = time.perf_counter() - t0
+    threads = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+    return {"value": tot / sec, "unit": "tokens/s", "cores": threads, "kind": "oracle",
+            "sample": f"first {tot} tokens of the same batch ({len(lens)} sequences), full model widths and vocab, "
+                      f"{sec:.1f} s of fp64 numpy work", "loss": out["loss"]}
+
+
+if __name__ == "__main__":
+    main()

@@ -90,6 +90,19 @@ ms_status ms_k_attention_backward(int32_t dtype, int32_t causal, int32_t n_q_hea
                                   const float *lse, const void *d_o, void *dqkv, void *scratch,
                                   void *stream);
 
+/* Per-kernel timing for roofline reports.  ms_profile_enable(1) makes the launchers bracket each
+ * kernel launch with HIP events on the launch stream (host-side objects only; at most 16384
+ * launches are kept, later ones are not recorded); ms_profile_enable(0) stops recording and
+ * frees the events.  ms_profile_read synchronises the recorded events and returns, for one
+ * kernel class, the number of launches, their summed duration in milliseconds and their summed
+ * algorithmic work (flops for matrix-core kernels, bytes for memory-bound kernels).
+ * Classes: 0 gemm NT, 1 gemm NN/TN/TT, 2 attention forward, 3 attention backward, 4 norm forward,
+ * 5 norm backward, 6 activation forward, 7 activation backward, 8 rotary embedding,
+ * 9 KD statistics, 10 KD logit gradient, 11 embedding / column sums / conversions. */
+#define MS_PROFILE_CLASSES 12
+ms_status ms_profile_enable(int32_t on);
+ms_status ms_profile_read(int32_t kernel_class, int64_t *launches, double *total_ms, double *total_work);
+
 /* Plain device copy of `bytes` bytes (a known-traffic kernel for calibrating counters). */
 ms_status ms_k_copy(const void *src, void *dst, size_t bytes, void *stream);
 

@@ -41,10 +41,15 @@ def attention_fwd(q, k, v, cu_seqlens, causal):
     return o
 
 
-def attention_bwd(do, q, k, v, cu_seqlens, causal):
+def attention_bwd(do, q, k, v, cu_seqlens, causal, o=None):
     """Gradients of attention_fwd: dV = P^T dO, dP = dO V^T,
-    dS = P * (dP - rowsum(dP * P)), dQ = dS K / sqrt(hd), dK = dS^T Q / sqrt(hd);
-    dK and dV are summed over the query heads that share a KV head."""
+    dS = P * (dP - delta), dQ = dS K / sqrt(hd), dK = dS^T Q / sqrt(hd);
+    dK and dV are summed over the query heads that share a KV head.
+
+    delta is the softmax-Jacobian row term rowsum(dP * P).  Because O = P V it also equals
+    rowsum(dO * O); when the stored forward output `o` is passed (the backward pass of a
+    section reads the output tensor the forward pass stored, rounded under the bf16
+    contract) that second form is used, otherwise the first."""
     n, nq, hd = q.shape
     nkv = k.shape[1]
     grp = nq // nkv
@@ -63,7 +68,11 @@ def attention_bwd(do, q, k, v, cu_seqlens, causal):
             doh = do[s0:s1, h]
             dv[s0:s1, g] += p.T @ doh
             dp = doh @ v[s0:s1, g].T
-            ds = p * (dp - np.sum(dp * p, axis=1, keepdims=True))
+            if o is None:
+                delta = np.sum(dp * p, axis=1, keepdims=True)
+            else:
+                delta = np.sum(doh * o[s0:s1, h], axis=1, keepdims=True)
+            ds = p * (dp - delta)
             dq[s0:s1, h] = (ds @ k[s0:s1, g]) * scale
             dk[s0:s1, g] += (ds.T @ q[s0:s1, h]) * scale
     return dq, dk, dv

@@ -12,7 +12,10 @@ and a final norm produces the hidden states that leave the section (only
 hidden states, never logits, cross a section boundary: Sec. 3.1).
 
 `rnd` is applied exactly where the bf16 HIP path stores a tensor between
-kernels; with `rnd=identity` everything is plain float64.
+kernels; `rnd_res` (default: the same as `rnd`) is applied to the residual
+stream (layer inputs / outputs and the post-attention sum), which a path may
+keep in higher precision than the other activations.  With `rnd=identity`
+everything is plain float64.
 """
 from dataclasses import dataclass
 
@@ -53,12 +56,13 @@ def _norm_bwd(spec, dy, x, stats, g):
     return ops.layernorm_bwd(dy, x, mu, r, g)
 
 
-def section_forward(spec, weights, cu_seqlens, x_in, rnd=identity, keep=False):
+def section_forward(spec, weights, cu_seqlens, x_in, rnd=identity, keep=False, rnd_res=None):
     """Returns h_out[N, d] (and the per-layer activations if keep=True)."""
+    rnd_res = rnd if rnd_res is None else rnd_res
     dec = spec.arch == "decoder"
     nq, nkv, hd = spec.n_q_heads, spec.n_kv_heads, spec.head_dim
     if spec.vocab > 0:
-        x = rnd(ops.embedding_fwd(x_in, weights["embedding"]))
+        x = rnd_res(ops.embedding_fwd(x_in, weights["embedding"]))
     else:
         x = np.asarray(x_in, dtype=np.float64)
     n = x.shape[0]
@@ -75,12 +79,12 @@ def section_forward(spec, weights, cu_seqlens, x_in, rnd=identity, keep=False):
             q = rnd(ops.rope_apply(q, pos, spec.rope_base))
             k = rnd(ops.rope_apply(k, pos, spec.rope_base))
         o = rnd(attention_fwd(q, k, v, cu_seqlens, causal=dec)).reshape(n, nq * hd)
-        x2 = rnd(x + ops.linear_fwd(o, lw["w_o"], lw.get("b_o")))
+        x2 = rnd_res(x + ops.linear_fwd(o, lw["w_o"], lw.get("b_o")))
         h2, st2 = _norm_fwd(spec, x2, lw["norm2_g"], lw.get("norm2_b"))
         h2 = rnd(h2)
         up = rnd(ops.linear_fwd(h2, lw["w_up"], lw.get("b_up")))
         a = rnd(ops.swiglu_fwd(up) if dec else ops.gelu_fwd(up))
-        y = rnd(x2 + ops.linear_fwd(a, lw["w_down"], lw.get("b_down")))
+        y = rnd_res(x2 + ops.linear_fwd(a, lw["w_down"], lw.get("b_down")))
         if keep:
             stash.append(dict(x=x, st1=st1, h1=h1, q=q, k=k, v=v, o=o, x2=x2, st2=st2, h2=h2, up=up, a=a))
         x = y
@@ -91,18 +95,19 @@ def section_forward(spec, weights, cu_seqlens, x_in, rnd=identity, keep=False):
     return h_out
 
 
-def section_backward(spec, weights, cu_seqlens, cache, d_h_out, rnd=identity):
+def section_backward(spec, weights, cu_seqlens, cache, d_h_out, rnd=identity, rnd_res=None):
     """Given dL/dh_out returns (grads, d_x_in): grads mirrors `weights` (float64,
     not rounded: weight gradients are accumulated in high precision), d_x_in is
     the gradient w.r.t. the input embeddings (None for a token-id section, whose
     input gradient is the embedding-table gradient)."""
+    rnd_res = rnd if rnd_res is None else rnd_res
     dec = spec.arch == "decoder"
     nq, nkv, hd = spec.n_q_heads, spec.n_kv_heads, spec.head_dim
     n = d_h_out.shape[0]
     grads = {"layers": [None] * spec.n_layers}
     dy, dg, db = _norm_bwd(spec, d_h_out, cache["y_last"], cache["stf"], weights["final_norm_g"])
     grads["final_norm_g"], grads["final_norm_b"] = dg, db
-    dy = rnd(dy)
+    dy = rnd_res(dy)
     for li in range(spec.n_layers - 1, -1, -1):
         lw, c = weights["layers"][li], cache["layers"][li]
         g = {}
@@ -113,10 +118,11 @@ def section_backward(spec, weights, cu_seqlens, cache, d_h_out, rnd=identity):
         dh2, g["w_up"], g["b_up"] = ops.linear_bwd(dup, c["h2"], lw["w_up"], bias)
         dh2 = rnd(dh2)
         dn, g["norm2_g"], g["norm2_b"] = _norm_bwd(spec, dh2, c["x2"], c["st2"], lw["norm2_g"])
-        dx2 = rnd(dy + dn)
+        dx2 = rnd_res(dy + dn)
         do, g["w_o"], g["b_o"] = ops.linear_bwd(dx2, c["o"], lw["w_o"], bias)
         do = rnd(do).reshape(n, nq, hd)
-        dq, dk, dv = attention_bwd(do, c["q"], c["k"], c["v"], cu_seqlens, causal=dec)
+        dq, dk, dv = attention_bwd(do, c["q"], c["k"], c["v"], cu_seqlens, causal=dec,
+                                   o=c["o"].reshape(n, nq, hd))
         dq, dk, dv = rnd(dq), rnd(dk), rnd(dv)
         if dec:
             dq = rnd(ops.rope_apply(dq, cache["pos"], spec.rope_base, inverse=True))
@@ -125,7 +131,7 @@ def section_backward(spec, weights, cu_seqlens, cache, d_h_out, rnd=identity):
         dh1, g["w_qkv"], g["b_qkv"] = ops.linear_bwd(dqkv, c["h1"], lw["w_qkv"], bias)
         dh1 = rnd(dh1)
         dn, g["norm1_g"], g["norm1_b"] = _norm_bwd(spec, dh1, c["x"], c["st1"], lw["norm1_g"])
-        dy = rnd(dx2 + dn)
+        dy = rnd_res(dx2 + dn)
         grads["layers"][li] = g
     if spec.vocab > 0:
         grads["embedding"] = ops.embedding_bwd(cache["x_in"], dy, spec.vocab)

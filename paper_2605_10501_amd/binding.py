@@ -332,3 +332,21 @@ def k_attention_backward(qkv, o, lse, d_o, batch, n_q_heads, n_kv_heads, head_di
 def k_copy(src, dst):
     _check(lib().ms_k_copy(_p(src), _p(dst), C.c_size_t(src.numel() * src.element_size()), _stream()))
     return dst
+
+
+PROFILE_CLASSES = ["gemm_nt", "gemm_t", "attn_fwd", "attn_bwd", "norm_fwd", "norm_bwd", "act_fwd", "act_bwd", "rope",
+                   "kd_stats", "kd_dz", "misc"]
+
+
+def profile_enable(on):
+    _check(lib().ms_profile_enable(int(on)))
+
+
+def profile_read():
+    """{class name: (launches, total_ms, total_work)} of the launches recorded since profile_enable(1)."""
+    out = {}
+    for i, name in enumerate(PROFILE_CLASSES):
+        n, ms, work = C.c_int64(0), C.c_double(0), C.c_double(0)
+        _check(lib().ms_profile_read(i, C.byref(n), C.byref(ms), C.byref(work)))
+        out[name] = (n.value, ms.value, work.value)
+    return out

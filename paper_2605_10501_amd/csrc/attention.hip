@@ -182,6 +182,7 @@ extern "C" ms_status ms_k_attention_forward(int32_t dtype, int32_t causal, int32
     if (!qkv || !o || !lse) return ms_fail(MS_ERR_INVALID_ARG, "attention_forward: null pointer");
     hipStream_t s = (hipStream_t)stream;
     const float scale = 1.f / sqrtf((float)hd);
+    ProfScope ps(2, 0.0, s);  // work (flops) depends on the sequence lengths: computed by the caller
     if (dtype == MS_BF16 && attn_mfma_supported(hd))
         return attn_mfma_forward(causal, nq, nkv, hd, n, n_seqs, max_seqlen, cu, qkv, o, lse, s);
     dim3 grid(n, ms_cdiv(nq, 4));
@@ -208,6 +209,7 @@ extern "C" ms_status ms_k_attention_backward(int32_t dtype, int32_t causal, int3
     if (!qkv || !o || !lse || !d_o || !dqkv || !scratch) return ms_fail(MS_ERR_INVALID_ARG, "attention_backward: null pointer");
     hipStream_t s = (hipStream_t)stream;
     const float scale = 1.f / sqrtf((float)hd);
+    ProfScope ps(3, 0.0, s);
     if (dtype == MS_BF16 && attn_mfma_supported(hd))
         return attn_mfma_backward(causal, nq, nkv, hd, n, n_seqs, max_seqlen, cu, qkv, o, lse, d_o, dqkv, scratch, s);
     float *dkv = (float *)scratch;

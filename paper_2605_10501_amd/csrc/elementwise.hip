@@ -396,6 +396,7 @@ extern "C" ms_status ms_k_norm_forward(int32_t kind, int32_t dtype, int32_t n, i
     if (d % V || !aligned16(x) || !aligned16(y) || !aligned16(g))
         return ms_fail(MS_ERR_UNSUPPORTED, "norm_forward: d=%d must be a multiple of %d and rows 16-byte aligned", d, V);
     hipStream_t s = (hipStream_t)stream;
+    ProfScope ps(4, 2.0 * n * d * (dtype == MS_BF16 ? 2 : 4), s);
     DISPATCH_T(dtype, {
         if (kind == 1)
             norm_fwd_kernel<T, 1><<<ms_cdiv(n, 4), 256, 0, s>>>((const T *)x, (const T *)g, (const T *)b, (T *)y, mean, rstd, n, d, eps);
@@ -431,12 +432,15 @@ extern "C" ms_status ms_k_norm_backward(int32_t kind, int32_t dtype, int32_t n, 
     float *pg = (float *)scratch;
     float *pb = (float *)((char *)scratch + ms_align_up((size_t)kPartialRows * d * sizeof(float)));
     const int grid = n / 4 < 1 ? 1 : (n / 4 > kPartialRows / 4 ? kPartialRows / 4 : n / 4);
+    {
+    ProfScope ps(5, (add ? 4.0 : 3.0) * n * d * (dtype == MS_BF16 ? 2 : 4), s);
     DISPATCH_T(dtype, {
         if (kind == 1)
             norm_bwd_kernel<T, 1><<<grid, 256, 0, s>>>((const T *)dy, (const T *)x, (const T *)g, mean, rstd, (const T *)add, (T *)dx, pg, pb, n, d);
         else
             norm_bwd_kernel<T, 0><<<grid, 256, 0, s>>>((const T *)dy, (const T *)x, (const T *)g, nullptr, rstd, (const T *)add, (T *)dx, pg, pb, n, d);
     });
+    }
     MS_LAUNCH_CHECK();
     MS_TRY(reduce_partials(pg, grid * 4, d, dg, s));
     if (kind == 1) MS_TRY(reduce_partials(pb, grid * 4, d, db, s));
@@ -482,6 +486,7 @@ extern "C" ms_status ms_k_rope(int32_t dtype, int32_t n, int32_t n_heads, int32_
     if (head_dim % (2 * V) || row_stride % V || !aligned16(x))
         return ms_fail(MS_ERR_UNSUPPORTED, "rope: head_dim=%d must be a multiple of %d", head_dim, 2 * V);
     const long total = (long)n * n_heads * (head_dim / 2 / V);
+    ProfScope ps(8, 2.0 * n * n_heads * head_dim * (dtype == MS_BF16 ? 2 : 4), (hipStream_t)stream);
     DISPATCH_T(dtype, {
         rope_kernel<T><<<ms_cdiv(total, 256), 256, 0, (hipStream_t)stream>>>((T *)x, pos, (const float2 *)table, total, n_heads, head_dim, row_stride, inverse ? -1.f : 1.f);
     });
@@ -496,6 +501,7 @@ extern "C" ms_status ms_k_act_forward(int32_t kind, int32_t dtype, int32_t n, in
     if (f % V) return ms_fail(MS_ERR_UNSUPPORTED, "act_forward: f=%d must be a multiple of %d", f, V);
     const long total = (long)n * (f / V);
     hipStream_t s = (hipStream_t)stream;
+    ProfScope ps(6, (kind == 0 ? 3.0 : 2.0) * n * f * (dtype == MS_BF16 ? 2 : 4), s);
     DISPATCH_T(dtype, {
         if (kind == 0) act_fwd_kernel<T, 0><<<ms_cdiv(total, 256), 256, 0, s>>>((const T *)up, (T *)a, total, f);
         else act_fwd_kernel<T, 1><<<ms_cdiv(total, 256), 256, 0, s>>>((const T *)up, (T *)a, total, f);
@@ -512,6 +518,7 @@ extern "C" ms_status ms_k_act_backward(int32_t kind, int32_t dtype, int32_t n, i
     if (f % V) return ms_fail(MS_ERR_UNSUPPORTED, "act_backward: f=%d must be a multiple of %d", f, V);
     const long total = (long)n * (f / V);
     hipStream_t s = (hipStream_t)stream;
+    ProfScope ps(7, (kind == 0 ? 5.0 : 3.0) * n * f * (dtype == MS_BF16 ? 2 : 4), s);
     DISPATCH_T(dtype, {
         if (kind == 0) act_bwd_kernel<T, 0><<<ms_cdiv(total, 256), 256, 0, s>>>((const T *)da, (const T *)up, (T *)dup, total, f);
         else act_bwd_kernel<T, 1><<<ms_cdiv(total, 256), 256, 0, s>>>((const T *)da, (const T *)up, (T *)dup, total, f);

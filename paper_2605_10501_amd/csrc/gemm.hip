@@ -169,8 +169,6 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmParams p) {
             sa.load(A, p.lda, m0, p.M, (kt_begin + kt + 1) * BK, k_end, tid);
             sb.load(B, p.ldb, n0, p.N, (kt_begin + kt + 1) * BK, k_end, tid);
         }
-        const bf16_t *at = As + cur * BM * BK + (wm * WTM) * BK;
-        const bf16_t *bt = Bs + cur * BN * BK + (wn * WTN) * BK;
 #pragma unroll
         for (int kk = 0; kk < BK / 16; ++kk) {
             bf16x8 af[MI], bfr[NI];
@@ -191,7 +189,6 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmParams p) {
                 for (int j = 0; j < NI; ++j)
                     acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bfr[j], acc[i][j], 0, 0, 0);
         }
-        (void)at; (void)bt;
         if (kt + 1 < nk) {
             sa.store(As + (cur ^ 1) * BM * BK, tid);
             sb.store(Bs + (cur ^ 1) * BN * BK, tid);
@@ -281,6 +278,7 @@ template <int BM, int BN>
 ms_status launch_bf16(const GemmParams &p, int ta, int tb, int splits, hipStream_t s) {
     const size_t smem = (size_t)2 * (BM + BN) * BK * sizeof(bf16_t);
     dim3 grid(p.tiles_m * p.tiles_n, splits);
+    ProfScope ps((ta || tb) ? 1 : 0, 2.0 * p.M * p.N * p.K, s);
 #define GO(TA, TB)                                                                                        \
     do {                                                                                                  \
         static bool attr_set = false;                                                                     \

@@ -177,14 +177,18 @@ ms_status kd_forward_backward(const ms_kd_config *kd, int n, const void *h_t, co
             MS_TRY(ms_k_gemm(dt, 0, 0, n, cw, Ht, 1.f, h_t, Ht, wt + (size_t)v0 * Ht * es, Ht, p.zt, Cv, 1, 0, nullptr, nullptr, 0, 1, s));
             MS_TRY(ms_k_gemm(dt, 0, 0, n, cw, Hs, 1.f, h_s, Hs, wsd + (size_t)v0 * Hs * es, Hs, p.zs, Cv, 1, 0, nullptr, nullptr, 0, 1, s));
             if (pass == 0) {
+                ProfScope ps(9, 8.0 * n * cw, s);
                 kd_stats_kernel<<<n, 256, 0, s>>>(p.zt, p.zs, Cv, cw, inv_t, v0 == 0, p.stats);
                 MS_LAUNCH_CHECK();
                 continue;
             }
             const float coef = kd->loss_scale * inv_t;
             dim3 grid(ms_cdiv(cw, 1024), n);
-            if (dt == MS_BF16) kd_dz_kernel<bf16_t><<<grid, 256, 0, s>>>(p.zt, p.zs, Cv, cw, inv_t, coef, p.stats, (bf16_t *)p.dz);
-            else kd_dz_kernel<float><<<grid, 256, 0, s>>>(p.zt, p.zs, Cv, cw, inv_t, coef, p.stats, (float *)p.dz);
+            {
+                ProfScope ps(10, (8.0 + es) * n * cw, s);
+                if (dt == MS_BF16) kd_dz_kernel<bf16_t><<<grid, 256, 0, s>>>(p.zt, p.zs, Cv, cw, inv_t, coef, p.stats, (bf16_t *)p.dz);
+                else kd_dz_kernel<float><<<grid, 256, 0, s>>>(p.zt, p.zs, Cv, cw, inv_t, coef, p.stats, (float *)p.dz);
+            }
             MS_LAUNCH_CHECK();
             if (d_h_s)  // dHs[N, Hs] += dz[N, cw] Ws_c[cw, Hs]
                 MS_TRY(ms_k_gemm(dt, 0, 1, n, Hs, cw, 1.f, p.dz, Cv, wsd + (size_t)v0 * Hs * es, Hs, p.dhs, Hs, 1, 1, nullptr, nullptr, 0, 1, s));

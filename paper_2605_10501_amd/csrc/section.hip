@@ -247,6 +247,8 @@ extern "C" ms_status ms_section_forward_backward(const ms_section_config *cfg, c
     MS_TRY(validate_config(cfg));
     int max_seqlen = 0;
     MS_TRY(validate_batch(batch, &max_seqlen));
+    hipStream_t s = (hipStream_t)stream;
+    if (batch->n_tokens == 0) return (kd && loss_dev) ? launch_fill_f32(loss_dev, 1, 0.f, s) : MS_OK;
     if ((d_h_out != nullptr) == (kd != nullptr))
         return ms_fail(MS_ERR_INVALID_ARG, "section_forward_backward: give exactly one of d_h_out and kd");
     if (kd) {
@@ -255,8 +257,6 @@ extern "C" ms_status ms_section_forward_backward(const ms_section_config *cfg, c
             return ms_fail(MS_ERR_SHAPE, "section_forward_backward: kd->h_student / dtype do not match the section");
         if (!loss_dev) return ms_fail(MS_ERR_INVALID_ARG, "section_forward_backward: loss_dev is null");
     }
-    hipStream_t s = (hipStream_t)stream;
-    if (batch->n_tokens == 0) return kd ? launch_fill_f32(loss_dev, 1, 0.f, s) : MS_OK;
     MS_TRY(validate_ptrs(cfg, weights, "weights"));
     MS_TRY(validate_ptrs(cfg, grads, "grads"));
     if (!x_in || !h_out || !workspace_dev || (kd && !h_teacher))

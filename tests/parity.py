@@ -1,7 +1,20 @@
 """Parity metric between the HIP path and the oracle.
 
-err_i = |gpu_i - ref_i| / max(|ref_i|, rms(ref)); every element must be within the tolerance.
-The rms floor makes the relative error meaningful for elements near zero.
+err_i = |gpu_i - ref_i| / max(|ref_i|, rms(ref)).  The rms floor makes the relative error
+meaningful for elements near zero.
+
+assert_parity: every element within the tolerance.  Used wherever the HIP result is one kernel
+(or one fp32 chain) away from inputs shared with the oracle.
+
+assert_parity_chain: for bf16 results that sit behind a chain of kernels with bf16 tensors in
+between.  Two correct bf16 pipelines do not stay in lock-step: an accumulator that lands on the
+other side of a bf16 rounding boundary differs by a whole ulp (2^-8 .. 2^-7 relative), the
+difference feeds the next kernels, and after a few stages the two runs carry independent
+rounding noise of about sqrt(stages) * 1.7e-3 relative (tests/test_oracle_section.py measures
+this between two oracle runs that differ by 1e-6 relative perturbations).  With ~4e-3 rms noise
+the 2e-2 bound is a 5-sigma event, so on tensors of 10^5 .. 10^7 elements a handful of elements
+may exceed it although nothing is wrong.  The chain criterion therefore requires
+  rms(err) <= tol / 4,  99.9 % of the elements <= tol,  every element <= 3 tol.
 """
 import numpy as np
 import torch
@@ -25,4 +38,15 @@ def assert_parity(gpu, ref, tol, name=""):
     assert np.all(np.isfinite(e)), f"{name}: non-finite values"
     mx = float(e.max()) if e.size else 0.0
     assert mx <= tol, f"{name}: max err {mx:.3e} > {tol:.1e} (p99.9 {np.quantile(e, 0.999):.3e}, at {np.unravel_index(e.argmax(), e.shape)})"
+    return mx
+
+
+def assert_parity_chain(gpu, ref, tol, name=""):
+    e = rel_err(gpu, ref)
+    assert np.all(np.isfinite(e)), f"{name}: non-finite values"
+    if e.size == 0:
+        return 0.0
+    mx, q, rms = float(e.max()), float(np.quantile(e, 0.999)), float(np.sqrt(np.mean(e * e)))
+    assert rms <= tol / 4 and q <= tol and mx <= 3 * tol, \
+        f"{name}: rms {rms:.3e} (<= {tol / 4:.1e}), p99.9 {q:.3e} (<= {tol:.1e}), max {mx:.3e} (<= {3 * tol:.1e})"
     return mx

@@ -107,6 +107,9 @@ def test_backward_finite_difference(rng, causal):
     c = rng.standard_normal((9, 4, 4))
     f = lambda: float(np.sum(c * attention_fwd(q, k, v, cu, causal)))
     dq, dk, dv = attention_bwd(c, q, k, v, cu, causal)
+    # the stored-output form of the row term (rowsum(dO * O)) is the same gradient
+    for a, b in zip((dq, dk, dv), attention_bwd(c, q, k, v, cu, causal, o=attention_fwd(q, k, v, cu, causal))):
+        assert np.allclose(a, b, atol=1e-13)
     for idx in [(0, 0, 0), (3, 1, 2), (5, 3, 1), (8, 2, 3)]:
         assert dq[idx] == pytest.approx(fd_grad(f, q, idx), rel=1e-6, abs=1e-9)
     for idx in [(0, 0, 0), (3, 1, 2), (5, 0, 1), (8, 1, 3)]:

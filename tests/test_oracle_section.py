@@ -150,3 +150,27 @@ def test_distill_step_end_to_end_gradient(rng):
     g_teacher = fd_grad(f, tw["layers"][0]["w_o"], (0, 0))
     assert g_teacher != 0.0     # the loss depends on the teacher, yet no gradient is produced for it
     assert "teacher_grads" not in out
+
+
+def test_two_bf16_pipelines_decorrelate_to_rounding_noise():
+    """Why chained bf16 results are compared statistically (see parity.assert_parity_chain):
+    two runs of the SAME bf16-contract oracle whose only difference is a 1e-6 relative
+    perturbation before each rounding (the size of an fp32-vs-fp64 accumulation difference) end
+    up differing by whole bf16 ulps on most elements after a few layers."""
+    from parity import rel_err, assert_parity_chain
+    spec = SectionSpec("decoder", 4, 64, 2, 1, 32, 96, vocab=50, norm_eps=1e-6, rope_base=1e4)
+    rng = np.random.default_rng(5)
+    w = make_weights(rng, spec, scale=0.05)
+    w["embedding"] = 0.05 * w["embedding"]
+    rb = lambda t: round_bf16(t)
+    w = {k: (rb(v) if k != "layers" else [{n: rb(a) for n, a in lw.items()} for lw in v]) for k, v in w.items()}
+    cu, ids = [0, 40, 100, 256], rng.integers(0, 50, 256)
+    noise = np.random.default_rng(6)
+    pert = lambda t: round_bf16(np.asarray(t) * (1 + 1e-6 * noise.standard_normal(np.shape(t))))
+    a = section_forward(spec, w, cu, ids, round_bf16)
+    b = section_forward(spec, w, cu, ids, pert)
+    e = rel_err(b, a)
+    assert np.mean(e > 0) > 0.3                      # not a few isolated flips: a third of all elements differ
+    assert 1e-3 < np.sqrt(np.mean(e * e)) < 5e-3     # at the level of a few bf16 roundings
+    assert e.max() > 7e-3                            # whole-ulp differences
+    assert_parity_chain(b, a, 2e-2, "perturbed bf16 oracle vs bf16 oracle")
