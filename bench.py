@@ -152,7 +152,7 @@ def cpu_baseline(work, tw, sw, wt, ws, ids, sample_tokens):
     (sequences truncated to fit), all host threads numpy's BLAS uses."""
     import numpy as np
     from threadpoolctl import threadpool_info
-    from oracle import round_bf16
+    from oracle import round_bf16, round_f32
     from oracle.section import SectionSpec
     from oracle.step import distill_step
     from paper_2605_10501_amd import workloads as wl
@@ -170,7 +170,7 @@ def cpu_baseline(work, tw, sw, wt, ws, ids, sample_tokens):
     ids_h = ids[:tot].cpu().numpy()
     t0 = time.perf_counter()
     out = distill_step(spec(work.teacher), t_w, spec(work.student), s_w, cu, ids_h, w_t, w_s,
-                       work.kd.temperature, 1.0 / tot, round_bf16)
+                       work.kd.temperature, 1.0 / tot, round_bf16, rnd_res=round_f32)
     sec = time.perf_counter() - t0
     threads = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
     return {"value": tot / sec, "unit": "tokens/s", "cores": threads, "kind": "oracle",

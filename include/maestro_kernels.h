@@ -24,23 +24,25 @@ extern "C" {
  * trans_b = 0: B is [N,K] row-major (ldb); 1: B is stored [K,N] (ldb).
  * c_fp32: C is fp32 regardless of dtype.  accumulate (needs c_fp32): C += result; with
  * split_k > 1 the K range is divided over that many workgroups that add atomically.
- * bias / residual are `dtype` (NULL = none), residual has leading dimension ldr.
+ * bias / residual are `dtype` (NULL = none), residual has leading dimension ldr and is fp32
+ * instead if residual_fp32 != 0 (the residual stream of a bf16 section is kept in fp32).
  * bf16 needs K % 8 == 0 for a non-transposed operand, M (resp. N) % 8 == 0 for a
  * transposed one, and 16-byte aligned rows. */
 ms_status ms_k_gemm(int32_t dtype, int32_t trans_a, int32_t trans_b, int32_t M, int32_t N, int32_t K,
                     float alpha, const void *A, int64_t lda, const void *B, int64_t ldb, void *C,
                     int64_t ldc, int32_t c_fp32, int32_t accumulate, const void *bias,
-                    const void *residual, int64_t ldr, int32_t split_k, void *stream);
+                    const void *residual, int64_t ldr, int32_t residual_fp32, int32_t split_k, void *stream);
 
 /* kind 0: RMSNorm y = x rstd g; kind 1: LayerNorm y = (x - mean) rstd g + b.
- * mean (kind 1 only) and rstd are fp32 [n] outputs kept for the backward pass. */
-ms_status ms_k_norm_forward(int32_t kind, int32_t dtype, int32_t n, int32_t d, float eps,
+ * mean (kind 1 only) and rstd are fp32 [n] outputs kept for the backward pass.
+ * x_fp32 != 0: x is fp32 although dtype is bf16 (g, b, y stay bf16). */
+ms_status ms_k_norm_forward(int32_t kind, int32_t dtype, int32_t x_fp32, int32_t n, int32_t d, float eps,
                             const void *x, const void *g, const void *b, void *y, float *mean,
                             float *rstd, void *stream);
 /* dx = norm backward of dy (+ add, if add != NULL);  dg += sum_t dy xhat;  db += sum_t dy.
  * dg / db fp32 [d], accumulated.  scratch: fp32, ms_k_norm_backward_scratch_bytes(d). */
 size_t ms_k_norm_backward_scratch_bytes(int32_t d);
-ms_status ms_k_norm_backward(int32_t kind, int32_t dtype, int32_t n, int32_t d, const void *dy,
+ms_status ms_k_norm_backward(int32_t kind, int32_t dtype, int32_t x_fp32, int32_t n, int32_t d, const void *dy,
                              const void *x, const void *g, const float *mean, const float *rstd,
                              const void *add, void *dx, float *dg, float *db, void *scratch,
                              void *stream);
@@ -62,8 +64,9 @@ ms_status ms_k_act_forward(int32_t kind, int32_t dtype, int32_t n, int32_t f, co
 ms_status ms_k_act_backward(int32_t kind, int32_t dtype, int32_t n, int32_t f, const void *da,
                             const void *up, void *dup, void *stream);
 
-ms_status ms_k_embedding_forward(int32_t dtype, int32_t n, int32_t d, int32_t vocab, const int32_t *ids,
-                                 const void *table, void *x, void *stream);
+/* x[t, :] = table[ids[t], :]; out_fp32 != 0 widens a bf16 table row to fp32 on the way. */
+ms_status ms_k_embedding_forward(int32_t dtype, int32_t out_fp32, int32_t n, int32_t d, int32_t vocab,
+                                 const int32_t *ids, const void *table, void *x, void *stream);
 /* d_table[ids[t], :] += dx[t, :]  (fp32, atomic). */
 ms_status ms_k_embedding_backward(int32_t dtype, int32_t n, int32_t d, int32_t vocab, const int32_t *ids,
                                   const void *dx, float *d_table, void *stream);

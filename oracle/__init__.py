@@ -12,10 +12,12 @@ Every tensor is a float64 ndarray, row-major, packed `[N, features]` with
 `cu_seqlens[B+1]` giving sequence boundaries.  `rnd` arguments are the
 "materialisation rounding": identity (pure fp64, used by the pins) or
 round-to-nearest-even to bf16 (used for parity with the bf16 HIP path, which
-stores exactly those tensors in bf16 while accumulating in fp32).
+stores exactly those tensors in bf16 while accumulating in fp32); `rnd_res`
+is the same for the forward residual stream, which the bf16 HIP path keeps in
+fp32 (round_f32).
 
 Parity status: the paper prints no worked numeric example of this path, so the
 oracle is pinned by closed forms, invariants, brute force on tiny inputs and
 finite differences (tests/test_oracle_*.py); no function here is unpinned.
 """
-from .rounding import identity, round_bf16  # noqa: F401
+from .rounding import identity, round_bf16, round_f32  # noqa: F401

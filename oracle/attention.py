@@ -16,29 +16,37 @@ def _softmax_rows(s):
     return e / np.sum(e, axis=1, keepdims=True)
 
 
-def _probs(qh, kh, causal):
+def _scores(qh, kh, causal):
     L, hd = qh.shape
     s = (qh @ kh.T) / np.sqrt(float(hd))
     if causal:
         s = np.where(np.tril(np.ones((L, L), dtype=bool)), s, -np.inf)
-    return _softmax_rows(s)
+    return s
 
 
-def attention_fwd(q, k, v, cu_seqlens, causal):
-    """q[N, nq, hd], k/v[N, nkv, hd] -> o[N, nq, hd]."""
+def _probs(qh, kh, causal):
+    return _softmax_rows(_scores(qh, kh, causal))
+
+
+def attention_fwd(q, k, v, cu_seqlens, causal, return_lse=False):
+    """q[N, nq, hd], k/v[N, nkv, hd] -> o[N, nq, hd] (and lse[nq, N], the natural-log
+    sum of exponentials of each query's visible scaled scores, if return_lse)."""
     n, nq, hd = q.shape
     nkv = k.shape[1]
     grp = nq // nkv
     o = np.zeros_like(q)
+    lse = np.zeros((nq, n), dtype=np.float64)
     cu = np.asarray(cu_seqlens, dtype=np.int64)
     for b in range(len(cu) - 1):
         s0, s1 = int(cu[b]), int(cu[b + 1])
         if s1 == s0:
             continue
         for h in range(nq):
-            p = _probs(q[s0:s1, h], k[s0:s1, h // grp], causal)
-            o[s0:s1, h] = p @ v[s0:s1, h // grp]
-    return o
+            s = _scores(q[s0:s1, h], k[s0:s1, h // grp], causal)
+            o[s0:s1, h] = _softmax_rows(s) @ v[s0:s1, h // grp]
+            mx = np.max(s, axis=1)
+            lse[h, s0:s1] = mx + np.log(np.sum(np.exp(s - mx[:, None]), axis=1))
+    return (o, lse) if return_lse else o
 
 
 def attention_bwd(do, q, k, v, cu_seqlens, causal, o=None):

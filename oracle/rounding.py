@@ -17,3 +17,8 @@ def round_bf16(x):
     u = f.view(np.uint32).astype(np.uint64)
     u = (u + 0x7FFF + ((u >> 16) & 1)) & 0xFFFF0000
     return u.astype(np.uint32).view(np.float32).astype(np.float64).reshape(np.shape(x))
+
+
+def round_f32(x):
+    """Round float64 -> float32 (round-to-nearest-even), return float64."""
+    return np.asarray(x, dtype=np.float64).astype(np.float32).astype(np.float64)

@@ -220,6 +220,7 @@ def pack_microbatches(lengths, token_budget, policy=0):
 # ------------------------------------------------------------------ kernel-level entry points
 def k_gemm(a, b, trans_a=False, trans_b=False, c=None, c_fp32=False, accumulate=False, bias=None, residual=None,
            alpha=1.0, split_k=1, dtype=None):
+    res_fp32 = residual is not None and residual.dtype == torch.float32 and a.dtype == torch.bfloat16
     """C[M,N] = alpha * A(m,k) B(n,k) (+bias) (+residual); a / b are 2-D tensors in their stored layout."""
     dt = _dt(dtype if dtype is not None else a.dtype)
     M, K = (a.shape[1], a.shape[0]) if trans_a else a.shape
@@ -229,27 +230,30 @@ def k_gemm(a, b, trans_a=False, trans_b=False, c=None, c_fp32=False, accumulate=
     _check(lib().ms_k_gemm(dt, int(trans_a), int(trans_b), M, N, K, C.c_float(alpha), _p(a), C.c_int64(a.stride(0)),
                            _p(b), C.c_int64(b.stride(0)), _p(c), C.c_int64(c.stride(0)), int(c_fp32), int(accumulate),
                            _p(bias), _p(residual), C.c_int64(residual.stride(0) if residual is not None else 0),
-                           split_k, _stream()))
+                           int(res_fp32), split_k, _stream()))
     return c
 
 
 def k_norm_forward(kind, x, g, b, eps):
+    """x may be fp32 while g / b / y are bf16 (fp32 residual stream of a bf16 section)."""
     n, d = x.shape
-    y = torch.empty_like(x)
+    y = torch.empty((n, d), dtype=g.dtype, device=x.device)
+    xf = int(x.dtype == torch.float32 and g.dtype == torch.bfloat16)
     rstd = torch.empty(n, dtype=torch.float32, device=x.device)
     mean = torch.empty(n, dtype=torch.float32, device=x.device) if kind == 1 else None
-    _check(lib().ms_k_norm_forward(kind, _dt(x.dtype), n, d, C.c_float(eps), _p(x), _p(g), _p(b), _p(y), _p(mean),
+    _check(lib().ms_k_norm_forward(kind, _dt(g.dtype), xf, n, d, C.c_float(eps), _p(x), _p(g), _p(b), _p(y), _p(mean),
                                    _p(rstd), _stream()))
     return y, mean, rstd
 
 
 def k_norm_backward(kind, dy, x, g, mean, rstd, add=None, dg=None, db=None):
     n, d = x.shape
-    dx = torch.empty_like(x)
+    dx = torch.empty_like(dy)
+    xf = int(x.dtype == torch.float32 and g.dtype == torch.bfloat16)
     dg = torch.zeros(d, dtype=torch.float32, device=x.device) if dg is None else dg
     db = (torch.zeros(d, dtype=torch.float32, device=x.device) if db is None else db) if kind == 1 else None
     sc = workspace(lib().ms_k_norm_backward_scratch_bytes(d), x.device, "norm")
-    _check(lib().ms_k_norm_backward(kind, _dt(x.dtype), n, d, _p(dy), _p(x), _p(g), _p(mean), _p(rstd), _p(add), _p(dx),
+    _check(lib().ms_k_norm_backward(kind, _dt(g.dtype), xf, n, d, _p(dy), _p(x), _p(g), _p(mean), _p(rstd), _p(add), _p(dx),
                                     _p(dg), _p(db), _p(sc), _stream()))
     return dx, dg, db
 
@@ -286,10 +290,10 @@ def k_act_backward(kind, da, up):
     return dup
 
 
-def k_embedding_forward(ids, table):
-    x = torch.empty((ids.shape[0], table.shape[1]), dtype=table.dtype, device=table.device)
-    _check(lib().ms_k_embedding_forward(_dt(table.dtype), ids.shape[0], table.shape[1], table.shape[0], _p(ids), _p(table),
-                                        _p(x), _stream()))
+def k_embedding_forward(ids, table, out_fp32=False):
+    x = torch.empty((ids.shape[0], table.shape[1]), dtype=torch.float32 if out_fp32 else table.dtype, device=table.device)
+    _check(lib().ms_k_embedding_forward(_dt(table.dtype), int(out_fp32), ids.shape[0], table.shape[1], table.shape[0],
+                                        _p(ids), _p(table), _p(x), _stream()))
     return x
 
 

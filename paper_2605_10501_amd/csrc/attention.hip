@@ -183,7 +183,7 @@ extern "C" ms_status ms_k_attention_forward(int32_t dtype, int32_t causal, int32
     hipStream_t s = (hipStream_t)stream;
     const float scale = 1.f / sqrtf((float)hd);
     ProfScope ps(2, 0.0, s);  // work (flops) depends on the sequence lengths: computed by the caller
-    if (dtype == MS_BF16 && attn_mfma_supported(hd))
+    if (dtype == MS_BF16 && attn_mfma_forward_supported(hd))
         return attn_mfma_forward(causal, nq, nkv, hd, n, n_seqs, max_seqlen, cu, qkv, o, lse, s);
     dim3 grid(n, ms_cdiv(nq, 4));
     if (dtype == MS_BF16)
@@ -196,7 +196,7 @@ extern "C" ms_status ms_k_attention_forward(int32_t dtype, int32_t causal, int32
 
 extern "C" size_t ms_k_attention_backward_scratch_bytes(int32_t dtype, int32_t nq, int32_t nkv, int32_t hd, int32_t n) {
     if (nq <= 0 || nkv <= 0 || hd <= 0 || n < 0) return 0;
-    if (dtype == MS_BF16 && attn_mfma_supported(hd)) return attn_mfma_backward_scratch_bytes(nq, nkv, hd, n);
+    if (dtype == MS_BF16 && attn_mfma_backward_supported(hd)) return attn_mfma_backward_scratch_bytes(nq, nkv, hd, n);
     return ms_align_up((size_t)n * 2 * nkv * hd * sizeof(float));
 }
 
@@ -210,7 +210,7 @@ extern "C" ms_status ms_k_attention_backward(int32_t dtype, int32_t causal, int3
     hipStream_t s = (hipStream_t)stream;
     const float scale = 1.f / sqrtf((float)hd);
     ProfScope ps(3, 0.0, s);
-    if (dtype == MS_BF16 && attn_mfma_supported(hd))
+    if (dtype == MS_BF16 && attn_mfma_backward_supported(hd))
         return attn_mfma_backward(causal, nq, nkv, hd, n, n_seqs, max_seqlen, cu, qkv, o, lse, d_o, dqkv, scratch, s);
     float *dkv = (float *)scratch;
     const long total = (long)n * 2 * nkv * hd;

@@ -10,8 +10,24 @@ constexpr int kMaxCache = 8;       // 16-byte vectors a lane keeps in registers 
 constexpr int kPartialRows = 1024; // rows of the partial-sum scratch of column reductions
 
 // ------------------------------------------------------------------ norm forward
-template <class T, int KIND>
-__global__ __launch_bounds__(256) void norm_fwd_kernel(const T *__restrict__ x, const T *__restrict__ g,
+// TX is the type of the normalised input (the residual stream: fp32 even for bf16 sections),
+// T the type of gains, shifts and of the output.  A lane handles V = 16 / sizeof(T) columns at a time.
+template <class TX, int V> __device__ __forceinline__ void load_row_vec(const TX *p, float *out) {
+    if constexpr (sizeof(TX) == 4) {
+#pragma unroll
+        for (int q = 0; q < V / 4; ++q) {
+            const float4 t = *(const float4 *)(p + 4 * q);
+            out[4 * q] = t.x; out[4 * q + 1] = t.y; out[4 * q + 2] = t.z; out[4 * q + 3] = t.w;
+        }
+    } else {
+        const Vec16<TX> t = ldv(p);
+#pragma unroll
+        for (int e = 0; e < V; ++e) out[e] = to_f32(t.v[e]);
+    }
+}
+
+template <class T, class TX, int KIND>
+__global__ __launch_bounds__(256) void norm_fwd_kernel(const TX *__restrict__ x, const T *__restrict__ g,
                                                         const T *__restrict__ b, T *__restrict__ y,
                                                         float *__restrict__ mean, float *__restrict__ rstd,
                                                         int n, int d, float eps) {
@@ -19,31 +35,30 @@ __global__ __launch_bounds__(256) void norm_fwd_kernel(const T *__restrict__ x, 
     const int lane = threadIdx.x & 63;
     const int row = blockIdx.x * 4 + (threadIdx.x >> 6);
     if (row >= n) return;
-    const T *xr = x + (size_t)row * d;
+    const TX *xr = x + (size_t)row * d;
     T *yr = y + (size_t)row * d;
     const int nvec = d / V;
-    Vec16<T> cache[kMaxCache];
+    float cache[kMaxCache][V];
     float s = 0.f, ss = 0.f;
 #pragma unroll
     for (int i = 0; i < kMaxCache; ++i) {
         int idx = lane + 64 * i;
         if (idx < nvec) {
-            cache[i] = ldv(xr + (size_t)idx * V);
+            load_row_vec<TX, V>(xr + (size_t)idx * V, cache[i]);
 #pragma unroll
             for (int e = 0; e < V; ++e) {
-                float f = to_f32(cache[i].v[e]);
-                s += f;
-                ss += f * f;
+                s += cache[i][e];
+                ss += cache[i][e] * cache[i][e];
             }
         }
     }
     for (int idx = lane + 64 * kMaxCache; idx < nvec; idx += 64) {
-        Vec16<T> t = ldv(xr + (size_t)idx * V);
+        float t[V];
+        load_row_vec<TX, V>(xr + (size_t)idx * V, t);
 #pragma unroll
         for (int e = 0; e < V; ++e) {
-            float f = to_f32(t.v[e]);
-            s += f;
-            ss += f * f;
+            s += t[e];
+            ss += t[e] * t[e];
         }
     }
     float mu = 0.f, var;
@@ -56,16 +71,17 @@ __global__ __launch_bounds__(256) void norm_fwd_kernel(const T *__restrict__ x, 
             if (idx < nvec) {
 #pragma unroll
                 for (int e = 0; e < V; ++e) {
-                    float f = to_f32(cache[i].v[e]) - mu;
+                    float f = cache[i][e] - mu;
                     sq += f * f;
                 }
             }
         }
         for (int idx = lane + 64 * kMaxCache; idx < nvec; idx += 64) {
-            Vec16<T> t = ldv(xr + (size_t)idx * V);
+            float t[V];
+            load_row_vec<TX, V>(xr + (size_t)idx * V, t);
 #pragma unroll
             for (int e = 0; e < V; ++e) {
-                float f = to_f32(t.v[e]) - mu;
+                float f = t[e] - mu;
                 sq += f * f;
             }
         }
@@ -78,12 +94,12 @@ __global__ __launch_bounds__(256) void norm_fwd_kernel(const T *__restrict__ x, 
         rstd[row] = r;
         if (KIND == 1) mean[row] = mu;
     }
-    auto emit = [&](int idx, const Vec16<T> &xv) {
+    auto emit = [&](int idx, const float *xv) {
         Vec16<T> gv = ldv(g + (size_t)idx * V), bv, out;
         if (KIND == 1) bv = ldv(b + (size_t)idx * V);
 #pragma unroll
         for (int e = 0; e < V; ++e) {
-            float f = (to_f32(xv.v[e]) - mu) * r * to_f32(gv.v[e]);
+            float f = (xv[e] - mu) * r * to_f32(gv.v[e]);
             if (KIND == 1) f += to_f32(bv.v[e]);
             out.v[e] = from_f32<T>(f);
         }
@@ -94,14 +110,18 @@ __global__ __launch_bounds__(256) void norm_fwd_kernel(const T *__restrict__ x, 
         int idx = lane + 64 * i;
         if (idx < nvec) emit(idx, cache[i]);
     }
-    for (int idx = lane + 64 * kMaxCache; idx < nvec; idx += 64) emit(idx, ldv(xr + (size_t)idx * V));
+    for (int idx = lane + 64 * kMaxCache; idx < nvec; idx += 64) {
+        float t[V];
+        load_row_vec<TX, V>(xr + (size_t)idx * V, t);
+        emit(idx, t);
+    }
 }
 
 // ------------------------------------------------------------------ norm backward
 // One wave per row, rows strided over the grid; each lane keeps the dg (and db) sums of its
 // columns in registers and finally writes one partial row per wave.
-template <class T, int KIND>
-__global__ __launch_bounds__(256) void norm_bwd_kernel(const T *__restrict__ dy, const T *__restrict__ x,
+template <class T, class TX, int KIND>
+__global__ __launch_bounds__(256) void norm_bwd_kernel(const T *__restrict__ dy, const TX *__restrict__ x,
                                                         const T *__restrict__ g, const float *__restrict__ mean,
                                                         const float *__restrict__ rstd, const T *__restrict__ add,
                                                         T *__restrict__ dx, float *__restrict__ part_g,
@@ -127,22 +147,23 @@ __global__ __launch_bounds__(256) void norm_bwd_kernel(const T *__restrict__ dy,
         const size_t ro = (size_t)row * d;
         const float r = rstd[row];
         const float mu = KIND == 1 ? mean[row] : 0.f;
-        Vec16<T> xv[kMaxCache], dv[kMaxCache];
+        float xh[kMaxCache][V];
+        Vec16<T> dv[kMaxCache];
         float c1 = 0.f, c2 = 0.f;
 #pragma unroll
         for (int i = 0; i < kMaxCache; ++i) {
             int idx = lane + 64 * i;
             if (idx < nvec) {
-                xv[i] = ldv(x + ro + (size_t)idx * V);
+                load_row_vec<TX, V>(x + ro + (size_t)idx * V, xh[i]);
                 dv[i] = ldv(dy + ro + (size_t)idx * V);
 #pragma unroll
                 for (int e = 0; e < V; ++e) {
-                    float xh = (to_f32(xv[i].v[e]) - mu) * r;
+                    xh[i][e] = (xh[i][e] - mu) * r;
                     float dyv = to_f32(dv[i].v[e]);
                     float t = dyv * to_f32(gv[i].v[e]);
-                    c1 += t * xh;
+                    c1 += t * xh[i][e];
                     c2 += t;
-                    accg[i][e] += dyv * xh;
+                    accg[i][e] += dyv * xh[i][e];
                     if constexpr (KIND == 1) accb[i][e] += dyv;
                 }
             }
@@ -157,9 +178,8 @@ __global__ __launch_bounds__(256) void norm_bwd_kernel(const T *__restrict__ dy,
                 if (add) av = ldv(add + ro + (size_t)idx * V);
 #pragma unroll
                 for (int e = 0; e < V; ++e) {
-                    float xh = (to_f32(xv[i].v[e]) - mu) * r;
                     float t = to_f32(dv[i].v[e]) * to_f32(gv[i].v[e]);
-                    float f = r * (t - c2 - xh * c1);
+                    float f = r * (t - c2 - xh[i][e] * c1);
                     if (add) f += to_f32(av.v[e]);
                     out.v[e] = from_f32<T>(f);
                 }
@@ -328,16 +348,24 @@ __global__ __launch_bounds__(256) void act_bwd_kernel(const T *__restrict__ da, 
 }
 
 // ------------------------------------------------------------------ embedding
-template <class T>
+template <class T, class TO>
 __global__ __launch_bounds__(256) void embedding_fwd_kernel(const int *__restrict__ ids, const T *__restrict__ table,
-                                                            T *__restrict__ x, long nvec_total, int d) {
+                                                            TO *__restrict__ x, long nvec_total, int d) {
     constexpr int V = Vec16<T>::N;
     long idx = (long)blockIdx.x * blockDim.x + threadIdx.x;
     if (idx >= nvec_total) return;
     const int vpr = d / V;
     long t = idx / vpr;
     int cv = idx % vpr;
-    stv(x + t * d + (long)cv * V, ldv(table + (long)ids[t] * d + (long)cv * V));
+    const Vec16<T> v = ldv(table + (long)ids[t] * d + (long)cv * V);
+    TO *o = x + t * d + (long)cv * V;
+    if constexpr (sizeof(TO) == sizeof(T)) {
+        stv(o, v);
+    } else {
+#pragma unroll
+        for (int q = 0; q < V / 4; ++q)
+            *(float4 *)(o + 4 * q) = make_float4(to_f32(v.v[4 * q]), to_f32(v.v[4 * q + 1]), to_f32(v.v[4 * q + 2]), to_f32(v.v[4 * q + 3]));
+    }
 }
 
 template <class T>
@@ -360,6 +388,12 @@ __global__ void fill_f32_kernel(float *p, long n, float v) {
     long i = (long)blockIdx.x * blockDim.x + threadIdx.x;
     long stride = (long)gridDim.x * blockDim.x;
     for (; i < n; i += stride) p[i] = v;
+}
+
+__global__ void convert_bf16_to_f32_kernel(const bf16_t *__restrict__ src, float *__restrict__ dst, long n) {
+    long i = (long)blockIdx.x * blockDim.x + threadIdx.x;
+    long stride = (long)gridDim.x * blockDim.x;
+    for (; i < n; i += stride) dst[i] = (float)src[i];
 }
 
 template <class T>
@@ -386,9 +420,9 @@ template <class T> constexpr int vec_of() { return 16 / sizeof(T); }
 
 static bool aligned16(const void *p) { return ((uintptr_t)p & 15) == 0; }
 
-extern "C" ms_status ms_k_norm_forward(int32_t kind, int32_t dtype, int32_t n, int32_t d, float eps, const void *x,
-                                       const void *g, const void *b, void *y, float *mean, float *rstd,
-                                       void *stream) {
+extern "C" ms_status ms_k_norm_forward(int32_t kind, int32_t dtype, int32_t x_fp32, int32_t n, int32_t d, float eps,
+                                       const void *x, const void *g, const void *b, void *y, float *mean,
+                                       float *rstd, void *stream) {
     if (n == 0) return MS_OK;
     if (!x || !g || !y || !rstd || (kind == 1 && (!b || !mean)) || n < 0 || d <= 0)
         return ms_fail(MS_ERR_INVALID_ARG, "norm_forward: null pointer or bad size");
@@ -396,13 +430,13 @@ extern "C" ms_status ms_k_norm_forward(int32_t kind, int32_t dtype, int32_t n, i
     if (d % V || !aligned16(x) || !aligned16(y) || !aligned16(g))
         return ms_fail(MS_ERR_UNSUPPORTED, "norm_forward: d=%d must be a multiple of %d and rows 16-byte aligned", d, V);
     hipStream_t s = (hipStream_t)stream;
-    ProfScope ps(4, 2.0 * n * d * (dtype == MS_BF16 ? 2 : 4), s);
-    DISPATCH_T(dtype, {
-        if (kind == 1)
-            norm_fwd_kernel<T, 1><<<ms_cdiv(n, 4), 256, 0, s>>>((const T *)x, (const T *)g, (const T *)b, (T *)y, mean, rstd, n, d, eps);
-        else
-            norm_fwd_kernel<T, 0><<<ms_cdiv(n, 4), 256, 0, s>>>((const T *)x, (const T *)g, nullptr, (T *)y, nullptr, rstd, n, d, eps);
-    });
+    const bool xf = x_fp32 || dtype == MS_F32;
+    ProfScope ps(4, (double)n * d * ((xf ? 4 : 2) + (dtype == MS_BF16 ? 2 : 4)), s);
+#define NORM_FWD(T, TX, K) norm_fwd_kernel<T, TX, K><<<ms_cdiv(n, 4), 256, 0, s>>>((const TX *)x, (const T *)g, (const T *)b, (T *)y, mean, rstd, n, d, eps)
+    if (dtype == MS_F32) { if (kind == 1) NORM_FWD(float, float, 1); else NORM_FWD(float, float, 0); }
+    else if (xf) { if (kind == 1) NORM_FWD(bf16_t, float, 1); else NORM_FWD(bf16_t, float, 0); }
+    else { if (kind == 1) NORM_FWD(bf16_t, bf16_t, 1); else NORM_FWD(bf16_t, bf16_t, 0); }
+#undef NORM_FWD
     MS_LAUNCH_CHECK();
     return MS_OK;
 }
@@ -417,8 +451,8 @@ static ms_status reduce_partials(const float *part, int np, int c, float *out, h
     return MS_OK;
 }
 
-extern "C" ms_status ms_k_norm_backward(int32_t kind, int32_t dtype, int32_t n, int32_t d, const void *dy,
-                                        const void *x, const void *g, const float *mean, const float *rstd,
+extern "C" ms_status ms_k_norm_backward(int32_t kind, int32_t dtype, int32_t x_fp32, int32_t n, int32_t d,
+                                        const void *dy, const void *x, const void *g, const float *mean, const float *rstd,
                                         const void *add, void *dx, float *dg, float *db, void *scratch,
                                         void *stream) {
     if (n == 0) return MS_OK;
@@ -433,13 +467,14 @@ extern "C" ms_status ms_k_norm_backward(int32_t kind, int32_t dtype, int32_t n, 
     float *pb = (float *)((char *)scratch + ms_align_up((size_t)kPartialRows * d * sizeof(float)));
     const int grid = n / 4 < 1 ? 1 : (n / 4 > kPartialRows / 4 ? kPartialRows / 4 : n / 4);
     {
-    ProfScope ps(5, (add ? 4.0 : 3.0) * n * d * (dtype == MS_BF16 ? 2 : 4), s);
-    DISPATCH_T(dtype, {
-        if (kind == 1)
-            norm_bwd_kernel<T, 1><<<grid, 256, 0, s>>>((const T *)dy, (const T *)x, (const T *)g, mean, rstd, (const T *)add, (T *)dx, pg, pb, n, d);
-        else
-            norm_bwd_kernel<T, 0><<<grid, 256, 0, s>>>((const T *)dy, (const T *)x, (const T *)g, nullptr, rstd, (const T *)add, (T *)dx, pg, pb, n, d);
-    });
+    const bool xf = x_fp32 || dtype == MS_F32;
+    const double es = dtype == MS_BF16 ? 2 : 4;
+    ProfScope ps(5, (double)n * d * ((xf ? 4 : 2) + (add ? 3.0 : 2.0) * es), s);
+#define NORM_BWD(T, TX, K) norm_bwd_kernel<T, TX, K><<<grid, 256, 0, s>>>((const T *)dy, (const TX *)x, (const T *)g, mean, rstd, (const T *)add, (T *)dx, pg, pb, n, d)
+    if (dtype == MS_F32) { if (kind == 1) NORM_BWD(float, float, 1); else NORM_BWD(float, float, 0); }
+    else if (xf) { if (kind == 1) NORM_BWD(bf16_t, float, 1); else NORM_BWD(bf16_t, float, 0); }
+    else { if (kind == 1) NORM_BWD(bf16_t, bf16_t, 1); else NORM_BWD(bf16_t, bf16_t, 0); }
+#undef NORM_BWD
     }
     MS_LAUNCH_CHECK();
     MS_TRY(reduce_partials(pg, grid * 4, d, dg, s));
@@ -527,14 +562,17 @@ extern "C" ms_status ms_k_act_backward(int32_t kind, int32_t dtype, int32_t n, i
     return MS_OK;
 }
 
-extern "C" ms_status ms_k_embedding_forward(int32_t dtype, int32_t n, int32_t d, int32_t vocab, const int32_t *ids,
-                                            const void *table, void *x, void *stream) {
+extern "C" ms_status ms_k_embedding_forward(int32_t dtype, int32_t out_fp32, int32_t n, int32_t d, int32_t vocab,
+                                            const int32_t *ids, const void *table, void *x, void *stream) {
     if (n == 0) return MS_OK;
     if (!ids || !table || !x || n < 0 || d <= 0 || vocab <= 0) return ms_fail(MS_ERR_INVALID_ARG, "embedding_forward: bad argument");
     const int V = dtype == MS_BF16 ? 8 : 4;
     if (d % V) return ms_fail(MS_ERR_UNSUPPORTED, "embedding: d=%d must be a multiple of %d", d, V);
     const long total = (long)n * (d / V);
-    DISPATCH_T(dtype, { embedding_fwd_kernel<T><<<ms_cdiv(total, 256), 256, 0, (hipStream_t)stream>>>(ids, (const T *)table, (T *)x, total, d); });
+    hipStream_t s = (hipStream_t)stream;
+    if (dtype == MS_F32) embedding_fwd_kernel<float, float><<<ms_cdiv(total, 256), 256, 0, s>>>(ids, (const float *)table, (float *)x, total, d);
+    else if (out_fp32) embedding_fwd_kernel<bf16_t, float><<<ms_cdiv(total, 256), 256, 0, s>>>(ids, (const bf16_t *)table, (float *)x, total, d);
+    else embedding_fwd_kernel<bf16_t, bf16_t><<<ms_cdiv(total, 256), 256, 0, s>>>(ids, (const bf16_t *)table, (bf16_t *)x, total, d);
     MS_LAUNCH_CHECK();
     return MS_OK;
 }
@@ -566,6 +604,14 @@ ms_status launch_fill_f32(float *p, long n, float v, hipStream_t s) {
     if (n <= 0) return MS_OK;
     const int grid = ms_cdiv(n, 256) > 8192 ? 8192 : ms_cdiv(n, 256);
     fill_f32_kernel<<<grid, 256, 0, s>>>(p, n, v);
+    MS_LAUNCH_CHECK();
+    return MS_OK;
+}
+
+ms_status launch_convert_bf16_to_f32(const void *src, float *dst, long n, hipStream_t s) {
+    if (n <= 0) return MS_OK;
+    const int grid = ms_cdiv(n, 256) > 16384 ? 16384 : ms_cdiv(n, 256);
+    convert_bf16_to_f32_kernel<<<grid, 256, 0, s>>>((const bf16_t *)src, dst, n);
     MS_LAUNCH_CHECK();
     return MS_OK;
 }

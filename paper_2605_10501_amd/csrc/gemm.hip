@@ -16,6 +16,7 @@
 // fp32: a plain LDS-tiled FMA kernel (correctness path of the fp32 workload).
 #include "common.h"
 #include "launch.h"
+#include "mfma_tiles.h"
 
 namespace {
 
@@ -28,87 +29,7 @@ struct GemmParams {
     int tiles_m, tiles_n;
     int k_tiles_per_split;  // in units of 64
     float alpha;
-    int c_fp32, accumulate, atomic;
-};
-
-constexpr int BK = 64;
-
-__device__ __forceinline__ int swz(int r, int c) { return c ^ ((r ^ (r >> 3)) & 7); }
-
-// element offset (in bf16) of 16-byte chunk c of row r in a [rows][64] tile
-__device__ __forceinline__ int lds_off(int r, int c) { return r * BK + swz(r, c) * 8; }
-
-__device__ __forceinline__ uint32_t pack_lo(uint32_t a, uint32_t b) { return (a & 0xffffu) | (b << 16); }
-__device__ __forceinline__ uint32_t pack_hi(uint32_t a, uint32_t b) { return (a >> 16) | (b & 0xffff0000u); }
-
-// Staging of one operand tile of ROWS x 64 (rows = m or n index, 64 = k).
-template <int ROWS, bool TRANS>
-struct Stager {
-    static constexpr int NREG = TRANS ? 8 * ((ROWS + 255) / 256) : ROWS / 32;
-    uint4 reg[NREG];
-
-    // P: base pointer; ld: leading dimension; row0: first m/n of the tile; rows_total: M or N;
-    // k0: first k of the tile; k_end: exclusive k bound.
-    __device__ __forceinline__ void load(const bf16_t *P, long ld, int row0, int rows_total, int k0, int k_end, int tid) {
-        if constexpr (!TRANS) {
-            const int c = tid & 7, r0 = tid >> 3;
-            const int k = k0 + c * 8;
-#pragma unroll
-            for (int i = 0; i < NREG; ++i) {
-                const int r = row0 + r0 + 32 * i;
-                if (r < rows_total && k < k_end) reg[i] = *(const uint4 *)(P + (long)r * ld + k);
-                else reg[i] = make_uint4(0, 0, 0, 0);
-            }
-        } else {
-            constexpr int MB = ROWS / 8;  // 8-row blocks along m
-#pragma unroll
-            for (int b = 0; b < (ROWS + 255) / 256; ++b) {
-                const int blk = tid + 256 * b;
-                const int mb = blk % MB, kb = blk / MB;
-                const int m = row0 + mb * 8;
-#pragma unroll
-                for (int j = 0; j < 8; ++j) {
-                    const int k = k0 + kb * 8 + j;
-                    if (blk < ROWS && m < rows_total && k < k_end) reg[b * 8 + j] = *(const uint4 *)(P + (long)k * ld + m);
-                    else reg[b * 8 + j] = make_uint4(0, 0, 0, 0);
-                }
-            }
-        }
-    }
-
-    __device__ __forceinline__ void store(bf16_t *tile, int tid) const {
-        if constexpr (!TRANS) {
-            const int c = tid & 7, r0 = tid >> 3;
-#pragma unroll
-            for (int i = 0; i < NREG; ++i) {
-                const int r = r0 + 32 * i;
-                *(uint4 *)(tile + lds_off(r, c)) = reg[i];
-            }
-        } else {
-            constexpr int MB = ROWS / 8;
-#pragma unroll
-            for (int b = 0; b < (ROWS + 255) / 256; ++b) {
-                const int blk = tid + 256 * b;
-                if (blk < ROWS) {
-                    const int mb = blk % MB, kb = blk / MB;
-                    const uint4 *in = &reg[b * 8];
-                    // in[j] = 8 m-values at k = j; out row i = 8 k-values at m = i
-#pragma unroll
-                    for (int i = 0; i < 8; ++i) {
-                        uint32_t w[4];
-#pragma unroll
-                        for (int pp = 0; pp < 4; ++pp) {
-                            const uint32_t a = ((const uint32_t *)&in[2 * pp])[i >> 1];
-                            const uint32_t bb = ((const uint32_t *)&in[2 * pp + 1])[i >> 1];
-                            w[pp] = (i & 1) ? pack_hi(a, bb) : pack_lo(a, bb);
-                        }
-                        const int r = mb * 8 + i;
-                        *(uint4 *)(tile + lds_off(r, kb)) = make_uint4(w[0], w[1], w[2], w[3]);
-                    }
-                }
-            }
-        }
-    }
+    int c_fp32, accumulate, atomic, res_fp32;
 };
 
 template <int BM, int BN, bool TA, bool TB>
@@ -198,6 +119,7 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmParams p) {
 
     // epilogue: acc[i][j][r] is C(row, col) with row = 8*(r/4) + 4*(lane/32) + r%4, col = lane%32
     const bf16_t *bias = (const bf16_t *)p.bias, *res = (const bf16_t *)p.residual;
+    const float *res32 = (const float *)p.residual;
 #pragma unroll
     for (int i = 0; i < MI; ++i)
 #pragma unroll
@@ -210,7 +132,7 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmParams p) {
                 const int row = m0 + wm * WTM + i * 32 + 8 * (r >> 2) + 4 * fhalf + (r & 3);
                 if (row >= p.M) continue;
                 float v = acc[i][j][r] * p.alpha + bv;
-                if (res) v += (float)res[(long)row * p.ldr + col];
+                if (res) v += p.res_fp32 ? res32[(long)row * p.ldr + col] : (float)res[(long)row * p.ldr + col];
                 if (p.c_fp32) {
                     float *c = (float *)p.C + (long)row * p.ldc + col;
                     if (p.atomic) unsafeAtomicAdd(c, v);
@@ -303,7 +225,8 @@ ms_status launch_bf16(const GemmParams &p, int ta, int tb, int splits, hipStream
 extern "C" ms_status ms_k_gemm(int32_t dtype, int32_t trans_a, int32_t trans_b, int32_t M, int32_t N, int32_t K,
                                float alpha, const void *A, int64_t lda, const void *B, int64_t ldb, void *C,
                                int64_t ldc, int32_t c_fp32, int32_t accumulate, const void *bias,
-                               const void *residual, int64_t ldr, int32_t split_k, void *stream) {
+                               const void *residual, int64_t ldr, int32_t residual_fp32, int32_t split_k,
+                               void *stream) {
     if (M == 0 || N == 0) return MS_OK;
     if (!A || !B || !C || M < 0 || N < 0 || K < 0) return ms_fail(MS_ERR_INVALID_ARG, "gemm: null pointer or negative size");
     if (accumulate && !c_fp32 && dtype == MS_BF16) return ms_fail(MS_ERR_INVALID_ARG, "gemm: accumulate needs an fp32 C");
@@ -327,7 +250,7 @@ extern "C" ms_status ms_k_gemm(int32_t dtype, int32_t trans_a, int32_t trans_b, 
     GemmParams p;
     p.A = A; p.B = B; p.C = C; p.bias = bias; p.residual = residual;
     p.lda = lda; p.ldb = ldb; p.ldc = ldc; p.ldr = ldr; p.M = M; p.N = N; p.K = K; p.alpha = alpha;
-    p.c_fp32 = c_fp32; p.accumulate = accumulate;
+    p.c_fp32 = c_fp32; p.accumulate = accumulate; p.res_fp32 = residual_fp32;
     constexpr int BM = 128, BN = 128;
     p.tiles_m = ms_cdiv(M, BM); p.tiles_n = ms_cdiv(N, BN);
     const int kt_total = ms_cdiv(K, BK) < 1 ? 1 : ms_cdiv(K, BK);

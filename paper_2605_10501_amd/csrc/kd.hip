@@ -174,8 +174,8 @@ ms_status kd_forward_backward(const ms_kd_config *kd, int n, const void *h_t, co
     for (int pass = 0; pass < passes; ++pass) {
         for (int v0 = 0; v0 < V; v0 += Cv) {
             const int cw = V - v0 < Cv ? V - v0 : Cv;
-            MS_TRY(ms_k_gemm(dt, 0, 0, n, cw, Ht, 1.f, h_t, Ht, wt + (size_t)v0 * Ht * es, Ht, p.zt, Cv, 1, 0, nullptr, nullptr, 0, 1, s));
-            MS_TRY(ms_k_gemm(dt, 0, 0, n, cw, Hs, 1.f, h_s, Hs, wsd + (size_t)v0 * Hs * es, Hs, p.zs, Cv, 1, 0, nullptr, nullptr, 0, 1, s));
+            MS_TRY(ms_k_gemm(dt, 0, 0, n, cw, Ht, 1.f, h_t, Ht, wt + (size_t)v0 * Ht * es, Ht, p.zt, Cv, 1, 0, nullptr, nullptr, 0, 0, 1, s));
+            MS_TRY(ms_k_gemm(dt, 0, 0, n, cw, Hs, 1.f, h_s, Hs, wsd + (size_t)v0 * Hs * es, Hs, p.zs, Cv, 1, 0, nullptr, nullptr, 0, 0, 1, s));
             if (pass == 0) {
                 ProfScope ps(9, 8.0 * n * cw, s);
                 kd_stats_kernel<<<n, 256, 0, s>>>(p.zt, p.zs, Cv, cw, inv_t, v0 == 0, p.stats);
@@ -191,9 +191,9 @@ ms_status kd_forward_backward(const ms_kd_config *kd, int n, const void *h_t, co
             }
             MS_LAUNCH_CHECK();
             if (d_h_s)  // dHs[N, Hs] += dz[N, cw] Ws_c[cw, Hs]
-                MS_TRY(ms_k_gemm(dt, 0, 1, n, Hs, cw, 1.f, p.dz, Cv, wsd + (size_t)v0 * Hs * es, Hs, p.dhs, Hs, 1, 1, nullptr, nullptr, 0, 1, s));
+                MS_TRY(ms_k_gemm(dt, 0, 1, n, Hs, cw, 1.f, p.dz, Cv, wsd + (size_t)v0 * Hs * es, Hs, p.dhs, Hs, 1, 1, nullptr, nullptr, 0, 0, 1, s));
             if (d_w_s)  // dWs_c[cw, Hs] += dz^T[cw, N] Hs[N, Hs]
-                MS_TRY(ms_k_gemm(dt, 1, 1, cw, Hs, n, 1.f, p.dz, Cv, h_s, Hs, (float *)d_w_s + (size_t)v0 * Hs, Hs, 1, 1, nullptr, nullptr, 0, 0, s));
+                MS_TRY(ms_k_gemm(dt, 1, 1, cw, Hs, n, 1.f, p.dz, Cv, h_s, Hs, (float *)d_w_s + (size_t)v0 * Hs, Hs, 1, 1, nullptr, nullptr, 0, 0, 0, s));
         }
         if (pass == 0) {
             kd_finalize_kernel<<<1, 1024, 0, s>>>(p.stats, n, kd->loss_scale, kl_tok_dev, loss_dev);

@@ -4,6 +4,7 @@
 
 ms_status launch_fill_f32(float *p, long n, float v, hipStream_t s);
 ms_status launch_convert_from_f32(int dtype, const float *src, void *dst, long n, hipStream_t s);
+ms_status launch_convert_bf16_to_f32(const void *src, float *dst, long n, hipStream_t s);
 
 // KD-loss pieces (kd.hip)
 ms_status kd_forward_backward(const ms_kd_config *kd, int n_tokens, const void *h_teacher, const void *h_student,

@@ -1,0 +1,89 @@
+// LDS tile helpers shared by the matrix-core kernels (GEMM and attention).
+//
+// A tile is [rows][64] bf16: 128-byte rows of eight 16-byte chunks, chunk c of row r stored at
+// chunk c ^ ((r ^ (r >> 3)) & 7).  Stager moves one such tile global -> registers -> LDS; for an
+// operand whose 64-wide dimension is the strided one in memory it transposes 8 x 8 blocks in
+// registers on the way.
+#pragma once
+#include "common.h"
+
+constexpr int BK = 64;
+
+__device__ __forceinline__ int swz(int r, int c) { return c ^ ((r ^ (r >> 3)) & 7); }
+
+// element offset (in bf16) of 16-byte chunk c of row r in a [rows][64] tile
+__device__ __forceinline__ int lds_off(int r, int c) { return r * BK + swz(r, c) * 8; }
+
+__device__ __forceinline__ uint32_t pack_lo(uint32_t a, uint32_t b) { return (a & 0xffffu) | (b << 16); }
+__device__ __forceinline__ uint32_t pack_hi(uint32_t a, uint32_t b) { return (a >> 16) | (b & 0xffff0000u); }
+
+// Staging of one operand tile of ROWS x 64 (rows = m or n index, 64 = k).
+template <int ROWS, bool TRANS>
+struct Stager {
+    static constexpr int NREG = TRANS ? 8 * ((ROWS + 255) / 256) : ROWS / 32;
+    uint4 reg[NREG];
+
+    // P: base pointer; ld: leading dimension; row0: first m/n of the tile; rows_total: M or N;
+    // k0: first k of the tile; k_end: exclusive k bound.
+    __device__ __forceinline__ void load(const bf16_t *P, long ld, int row0, int rows_total, int k0, int k_end, int tid) {
+        if constexpr (!TRANS) {
+            const int c = tid & 7, r0 = tid >> 3;
+            const int k = k0 + c * 8;
+#pragma unroll
+            for (int i = 0; i < NREG; ++i) {
+                const int r = row0 + r0 + 32 * i;
+                if (r < rows_total && k < k_end) reg[i] = *(const uint4 *)(P + (long)r * ld + k);
+                else reg[i] = make_uint4(0, 0, 0, 0);
+            }
+        } else {
+            constexpr int MB = ROWS / 8;  // 8-row blocks along m
+#pragma unroll
+            for (int b = 0; b < (ROWS + 255) / 256; ++b) {
+                const int blk = tid + 256 * b;
+                const int mb = blk % MB, kb = blk / MB;
+                const int m = row0 + mb * 8;
+#pragma unroll
+                for (int j = 0; j < 8; ++j) {
+                    const int k = k0 + kb * 8 + j;
+                    if (blk < ROWS && m < rows_total && k < k_end) reg[b * 8 + j] = *(const uint4 *)(P + (long)k * ld + m);
+                    else reg[b * 8 + j] = make_uint4(0, 0, 0, 0);
+                }
+            }
+        }
+    }
+
+    __device__ __forceinline__ void store(bf16_t *tile, int tid) const {
+        if constexpr (!TRANS) {
+            const int c = tid & 7, r0 = tid >> 3;
+#pragma unroll
+            for (int i = 0; i < NREG; ++i) {
+                const int r = r0 + 32 * i;
+                *(uint4 *)(tile + lds_off(r, c)) = reg[i];
+            }
+        } else {
+            constexpr int MB = ROWS / 8;
+#pragma unroll
+            for (int b = 0; b < (ROWS + 255) / 256; ++b) {
+                const int blk = tid + 256 * b;
+                if (blk < ROWS) {
+                    const int mb = blk % MB, kb = blk / MB;
+                    const uint4 *in = &reg[b * 8];
+                    // in[j] = 8 m-values at k = j; out row i = 8 k-values at m = i
+#pragma unroll
+                    for (int i = 0; i < 8; ++i) {
+                        uint32_t w[4];
+#pragma unroll
+                        for (int pp = 0; pp < 4; ++pp) {
+                            const uint32_t a = ((const uint32_t *)&in[2 * pp])[i >> 1];
+                            const uint32_t bb = ((const uint32_t *)&in[2 * pp + 1])[i >> 1];
+                            w[pp] = (i & 1) ? pack_hi(a, bb) : pack_lo(a, bb);
+                        }
+                        const int r = mb * 8 + i;
+                        *(uint4 *)(tile + lds_off(r, kb)) = make_uint4(w[0], w[1], w[2], w[3]);
+                    }
+                }
+            }
+        }
+    }
+};
+

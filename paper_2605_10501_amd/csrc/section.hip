@@ -1,8 +1,10 @@
 // Section executor: validates a call, carves the caller's workspace, and sequences the kernels
 // of a layer stack forward (teacher) or forward + backward (student / vision encoder).
 //
-// Tensors that live between kernels are stored in the section dtype; norm statistics, log-sum-
-// exps, weight gradients and the loss are fp32.  In forward+backward mode every layer keeps its
+// Tensors that live between kernels are stored in the section dtype, except the forward residual
+// stream (layer inputs, post-attention sums, last layer output), which is the running sum of all
+// branch outputs and is kept in fp32; norm statistics, log-sum-exps, weight gradients and the loss
+// are fp32 too.  In forward+backward mode every layer keeps its
 // input, both normed activations, the (rotated) qkv, the attention output and log-sum-exp, the
 // post-attention residual, the FFN pre-activation and activation: nothing is recomputed.
 #include <vector>
@@ -55,17 +57,18 @@ Plan make_plan(const ms_section_config *c, int n, int max_seqlen, bool bwd, void
     Plan p = {};
     const size_t N = (size_t)n;
     auto act = [&](size_t cols) { return a.take<void>(N * cols * m.es); };
+    auto res = [&](size_t cols) { return a.take<void>(N * cols * 4); };   // residual stream: fp32
     auto f32 = [&](size_t cnt) { return a.take<float>(cnt * 4); };
     const int nbuf = bwd ? c->n_layers : 1;
     p.layers.resize(nbuf);
     for (auto &l : p.layers) {
-        l.x = bwd ? act(m.d) : nullptr;
-        l.h1 = act(m.d); l.qkv = act(m.dqkv); l.o = act(m.dattn); l.x2 = act(m.d); l.h2 = act(m.d);
+        l.x = bwd ? res(m.d) : nullptr;
+        l.h1 = act(m.d); l.qkv = act(m.dqkv); l.o = act(m.dattn); l.x2 = res(m.d); l.h2 = act(m.d);
         l.up = act(m.dup); l.act = act(m.f);
         l.lse = f32(N * m.nq); l.rstd1 = f32(N); l.mean1 = f32(N); l.rstd2 = f32(N); l.mean2 = f32(N);
     }
-    if (!bwd) { p.xa = act(m.d); p.xb = act(m.d); }
-    p.y_last = act(m.d);
+    if (!bwd) { p.xa = res(m.d); p.xb = res(m.d); }
+    p.y_last = res(m.d);
     p.rstd_f = f32(N); p.mean_f = f32(N);
     p.pos = a.take<int32_t>(N * 4);
     p.rope = f32((size_t)max_seqlen * m.hd);  // [max_seqlen, hd/2] (cos, sin)
@@ -140,11 +143,12 @@ struct Exec {
 
     ms_status gemm(int ta, int tb, int M, int N, int K, const void *A, long lda, const void *B, long ldb, void *C,
                    long ldc, bool c_fp32, bool acc, const void *bias, const void *res, long ldr) {
-        return ms_k_gemm(dt, ta, tb, M, N, K, 1.f, A, lda, B, ldb, C, ldc, c_fp32, acc, bias, res, ldr, acc ? 0 : 1, s);
+        return ms_k_gemm(dt, ta, tb, M, N, K, 1.f, A, lda, B, ldb, C, ldc, c_fp32, acc, bias, res, ldr, res != nullptr,
+                         acc ? 0 : 1, s);
     }
-    // y[n, out] = x[n, in] W[out, in]^T (+ bias) (+ res)
+    // y[n, out] = x[n, in] W[out, in]^T (+ bias) (+ res); with a residual, res and y are the fp32 stream
     ms_status linear(const void *x, int in, const void *W, const void *bias, int out, void *y, const void *res) {
-        return gemm(0, 0, m.n, out, in, x, in, W, in, y, out, false, false, bias, res, out);
+        return gemm(0, 0, m.n, out, in, x, in, W, in, y, out, res != nullptr, false, bias, res, out);
     }
     // dx[n, in] = dy[n, out] W[out, in]
     ms_status dgrad(const void *dy, int out, const void *W, int in, void *dx) {
@@ -166,13 +170,13 @@ struct Exec {
     }
 
     ms_status layer_forward(const ms_layer_ptrs &w, const void *x, LayerBuf &l, void *y) {
-        MS_TRY(ms_k_norm_forward(kind, dt, m.n, m.d, c->norm_eps, x, w.norm1_g, w.norm1_b, l.h1, l.mean1, l.rstd1, s));
+        MS_TRY(ms_k_norm_forward(kind, dt, 1, m.n, m.d, c->norm_eps, x, w.norm1_g, w.norm1_b, l.h1, l.mean1, l.rstd1, s));
         MS_TRY(linear(l.h1, m.d, w.w_qkv, m.dec ? nullptr : w.b_qkv, m.dqkv, l.qkv, nullptr));
         if (m.dec) MS_TRY(ms_k_rope(dt, m.n, m.nq + m.nkv, m.hd, m.dqkv, l.qkv, p->pos, p->rope, 0, s));
         MS_TRY(ms_k_attention_forward(dt, m.dec, m.nq, m.nkv, m.hd, m.n, b->n_seqs, m.max_seqlen, b->cu_seqlens_dev,
                                       l.qkv, l.o, l.lse, s));
         MS_TRY(linear(l.o, m.dattn, w.w_o, m.dec ? nullptr : w.b_o, m.d, l.x2, x));
-        MS_TRY(ms_k_norm_forward(kind, dt, m.n, m.d, c->norm_eps, l.x2, w.norm2_g, w.norm2_b, l.h2, l.mean2, l.rstd2, s));
+        MS_TRY(ms_k_norm_forward(kind, dt, 1, m.n, m.d, c->norm_eps, l.x2, w.norm2_g, w.norm2_b, l.h2, l.mean2, l.rstd2, s));
         MS_TRY(linear(l.h2, m.d, w.w_up, m.dec ? nullptr : w.b_up, m.dup, l.up, nullptr));
         MS_TRY(ms_k_act_forward(m.dec ? 0 : 1, dt, m.n, m.f, l.up, l.act, s));
         MS_TRY(linear(l.act, m.f, w.w_down, m.dec ? nullptr : w.b_down, m.d, y, l.x2));
@@ -186,7 +190,7 @@ struct Exec {
         MS_TRY(ms_k_act_backward(m.dec ? 0 : 1, dt, m.n, m.f, p->da, l.up, p->dup, s));
         MS_TRY(dgrad(p->dup, m.dup, w.w_up, m.d, p->dh));
         MS_TRY(wgrad(p->dup, m.dup, l.h2, m.d, g.w_up, g.b_up));
-        MS_TRY(ms_k_norm_backward(kind, dt, m.n, m.d, p->dh, l.x2, w.norm2_g, l.mean2, l.rstd2, dy, p->dx2,
+        MS_TRY(ms_k_norm_backward(kind, dt, 1, m.n, m.d, p->dh, l.x2, w.norm2_g, l.mean2, l.rstd2, dy, p->dx2,
                                   (float *)g.norm2_g, (float *)g.norm2_b, p->norm_scratch, s));
         MS_TRY(dgrad(p->dx2, m.d, w.w_o, m.dattn, p->d_o));
         MS_TRY(wgrad(p->dx2, m.d, l.o, m.dattn, g.w_o, g.b_o));
@@ -195,7 +199,7 @@ struct Exec {
         if (m.dec) MS_TRY(ms_k_rope(dt, m.n, m.nq + m.nkv, m.hd, m.dqkv, p->dqkv, p->pos, p->rope, 1, s));
         MS_TRY(dgrad(p->dqkv, m.dqkv, w.w_qkv, m.d, p->dh));
         MS_TRY(wgrad(p->dqkv, m.dqkv, l.h1, m.d, g.w_qkv, g.b_qkv));
-        MS_TRY(ms_k_norm_backward(kind, dt, m.n, m.d, p->dh, l.x, w.norm1_g, l.mean1, l.rstd1, p->dx2, dx,
+        MS_TRY(ms_k_norm_backward(kind, dt, 1, m.n, m.d, p->dh, l.x, w.norm1_g, l.mean1, l.rstd1, p->dx2, dx,
                                   (float *)g.norm1_g, (float *)g.norm1_b, p->norm_scratch, s));
         return MS_OK;
     }
@@ -226,7 +230,10 @@ extern "C" ms_status ms_section_forward(const ms_section_config *cfg, const ms_s
     MS_TRY(e.prologue());
     const void *x = x_in;
     if (cfg->vocab > 0) {
-        MS_TRY(ms_k_embedding_forward(e.dt, e.m.n, e.m.d, cfg->vocab, (const int32_t *)x_in, weights->embedding, p.xa, e.s));
+        MS_TRY(ms_k_embedding_forward(e.dt, 1, e.m.n, e.m.d, cfg->vocab, (const int32_t *)x_in, weights->embedding, p.xa, e.s));
+        x = p.xa;
+    } else if (e.dt == MS_BF16) {
+        MS_TRY(launch_convert_bf16_to_f32(x_in, (float *)p.xa, (long)e.m.n * e.m.d, e.s));
         x = p.xa;
     }
     for (int li = 0; li < cfg->n_layers; ++li) {
@@ -234,7 +241,7 @@ extern "C" ms_status ms_section_forward(const ms_section_config *cfg, const ms_s
         MS_TRY(e.layer_forward(weights->layers[li], x, p.layers[0], y));
         x = y;
     }
-    return ms_k_norm_forward(e.kind, e.dt, e.m.n, e.m.d, cfg->norm_eps, x, weights->final_norm_g, weights->final_norm_b,
+    return ms_k_norm_forward(e.kind, e.dt, 1, e.m.n, e.m.d, cfg->norm_eps, x, weights->final_norm_g, weights->final_norm_b,
                              h_out, p.mean_f, p.rstd_f, e.s);
 }
 
@@ -270,7 +277,10 @@ extern "C" ms_status ms_section_forward_backward(const ms_section_config *cfg, c
     const int L = cfg->n_layers;
     const void *x = x_in;
     if (cfg->vocab > 0) {
-        MS_TRY(ms_k_embedding_forward(e.dt, e.m.n, e.m.d, cfg->vocab, (const int32_t *)x_in, weights->embedding, p.layers[0].x, s));
+        MS_TRY(ms_k_embedding_forward(e.dt, 1, e.m.n, e.m.d, cfg->vocab, (const int32_t *)x_in, weights->embedding, p.layers[0].x, s));
+        x = p.layers[0].x;
+    } else if (e.dt == MS_BF16) {
+        MS_TRY(launch_convert_bf16_to_f32(x_in, (float *)p.layers[0].x, (long)e.m.n * e.m.d, s));
         x = p.layers[0].x;
     }
     for (int li = 0; li < L; ++li) {
@@ -279,7 +289,7 @@ extern "C" ms_status ms_section_forward_backward(const ms_section_config *cfg, c
         MS_TRY(e.layer_forward(weights->layers[li], x, p.layers[li], y));
         x = y;
     }
-    MS_TRY(ms_k_norm_forward(e.kind, e.dt, e.m.n, e.m.d, cfg->norm_eps, p.y_last, weights->final_norm_g,
+    MS_TRY(ms_k_norm_forward(e.kind, e.dt, 1, e.m.n, e.m.d, cfg->norm_eps, p.y_last, weights->final_norm_g,
                              weights->final_norm_b, h_out, p.mean_f, p.rstd_f, s));
     const void *dh = d_h_out;
     if (kd) {
@@ -288,7 +298,7 @@ extern "C" ms_status ms_section_forward_backward(const ms_section_config *cfg, c
         dh = p.dhs;
     }
     void *dy = p.dy0;
-    MS_TRY(ms_k_norm_backward(e.kind, e.dt, e.m.n, e.m.d, dh, p.y_last, weights->final_norm_g, p.mean_f, p.rstd_f, nullptr,
+    MS_TRY(ms_k_norm_backward(e.kind, e.dt, 1, e.m.n, e.m.d, dh, p.y_last, weights->final_norm_g, p.mean_f, p.rstd_f, nullptr,
                               dy, (float *)grads->final_norm_g, (float *)grads->final_norm_b, p.norm_scratch, s));
     for (int li = L - 1; li >= 0; --li) {
         void *dx = (li == 0 && cfg->vocab == 0 && d_x_in) ? d_x_in : (dy == p.dy0 ? p.dy1 : p.dy0);

@@ -14,7 +14,7 @@ rounding noise of about sqrt(stages) * 1.7e-3 relative (tests/test_oracle_sectio
 this between two oracle runs that differ by 1e-6 relative perturbations).  With ~4e-3 rms noise
 the 2e-2 bound is a 5-sigma event, so on tensors of 10^5 .. 10^7 elements a handful of elements
 may exceed it although nothing is wrong.  The chain criterion therefore requires
-  rms(err) <= tol / 4,  99.9 % of the elements <= tol,  every element <= 3 tol.
+  rms(err) <= tol / 3,  99.9 % of the elements <= tol,  every element <= 3 tol.
 """
 import numpy as np
 import torch
@@ -47,6 +47,6 @@ def assert_parity_chain(gpu, ref, tol, name=""):
     if e.size == 0:
         return 0.0
     mx, q, rms = float(e.max()), float(np.quantile(e, 0.999)), float(np.sqrt(np.mean(e * e)))
-    assert rms <= tol / 4 and q <= tol and mx <= 3 * tol, \
-        f"{name}: rms {rms:.3e} (<= {tol / 4:.1e}), p99.9 {q:.3e} (<= {tol:.1e}), max {mx:.3e} (<= {3 * tol:.1e})"
+    assert rms <= tol / 3 and q <= tol and mx <= 3 * tol, \
+        f"{name}: rms {rms:.3e} (<= {tol / 3:.1e}), p99.9 {q:.3e} (<= {tol:.1e}), max {mx:.3e} (<= {3 * tol:.1e})"
     return mx

@@ -47,6 +47,9 @@ def test_gemm_epilogues_and_split_k():
     bias, res = dev("ebias", (N,), torch.bfloat16), dev("eres", (M, N), torch.bfloat16)
     ref = 0.5 * (f64(a) @ f64(b).T) + f64(bias)[None, :] + f64(res)
     assert_parity(B.k_gemm(a, b, bias=bias, residual=res, alpha=0.5), round_bf16(ref), TOL_BF16, "bias+res")
+    res32 = dev("eres32", (M, N), torch.float32)   # fp32 residual stream in, fp32 out
+    ref32 = f64(a) @ f64(b).T + f64(bias)[None, :] + f64(res32)
+    assert_parity(B.k_gemm(a, b, bias=bias, residual=res32, c_fp32=True), ref32, TOL_F32, "fp32 residual")
     c0 = dev("ec", (M, N), torch.float32)
     for split in (1, 4, 0):
         c = c0.clone()
@@ -93,6 +96,20 @@ def test_norm_forward_backward(dtype, kind, d):
     assert_parity(dg, dgr, 2e-4, "dg")
     if kind:
         assert_parity(db, dbr, 2e-4, "db")
+    if dtype == torch.bfloat16:  # fp32 residual-stream input with bf16 gains / output
+        x32 = dev("nx32", (n, d), torch.float32, 2.0, 0.3)
+        y32, mean32, rstd32 = B.k_norm_forward(kind, x32, g, b if kind else None, eps)
+        if kind == 0:
+            yr32, r32 = ops.rmsnorm_fwd(f64(x32), f64(g), eps)
+            dxr32, dgr32 = ops.rmsnorm_bwd(f64(dy), f64(x32), r32, f64(g))
+        else:
+            yr32, mu32, r32 = ops.layernorm_fwd(f64(x32), f64(g), f64(b), eps)
+            dxr32, dgr32, _ = ops.layernorm_bwd(f64(dy), f64(x32), mu32, r32, f64(g))
+        assert y32.dtype == torch.bfloat16
+        assert_parity(y32, rnd(yr32), tol, "y from fp32 x")
+        dx32, dg32, _ = B.k_norm_backward(kind, dy, x32, g, mean32, rstd32, add)
+        assert_parity(dx32, rnd(dxr32 + f64(add)), tol, "dx from fp32 x")
+        assert_parity(dg32, dgr32, 2e-4, "dg from fp32 x")
     dg2 = dg.clone()
     B.k_norm_backward(kind, dy, x, g, mean, rstd, None, dg2, db.clone() if kind else None)
     assert_parity(dg2, 2 * dgr, 2e-4, "dg accumulates")
@@ -141,6 +158,7 @@ def test_embedding_and_colsum(dtype):
     table, dx = dev("et", (vocab, d), dtype), dev("edx", (n, d), dtype)
     ids = wl.randint(7, "ids", n, 0, vocab, "cuda")
     assert torch.equal(B.k_embedding_forward(ids, table), table[ids.long()])
+    assert torch.equal(B.k_embedding_forward(ids, table, out_fp32=True), table[ids.long()].float())
     assert_parity(B.k_embedding_backward(ids, dx, vocab), ops.embedding_bwd(ids.cpu().numpy(), f64(dx), vocab), 2e-4)
     assert_parity(B.k_colsum(dx), f64(dx).sum(axis=0), 2e-4, "colsum")
 
@@ -166,11 +184,20 @@ def test_attention_forward_backward(dtype, causal, nq, nkv, hd, cu, sharp):
     k = f64(qkv)[:, nq * hd:(nq + nkv) * hd].reshape(n, nkv, hd)
     v = f64(qkv)[:, (nq + nkv) * hd:].reshape(n, nkv, hd)
     rnd, tol = rnd_of(dtype), tol_of(dtype)
+    if dtype == torch.float32 and sharp > 1:
+        tol = 5e-4   # scores of magnitude ~2^7 carry ~2^-17 absolute fp32 error, which exp() turns into relative error
     o, lse = B.k_attention_forward(qkv, batch, nq, nkv, hd, causal)
-    o_ref = rnd(attention_fwd(q, k, v, cu, causal))
+    o_ref, lse_ref = attention_fwd(q, k, v, cu, causal, return_lse=True)
+    o_ref = rnd(o_ref)
+    o, lse = B.k_attention_forward(qkv, batch, nq, nkv, hd, causal)
     assert_parity(o, o_ref.reshape(n, -1), tol, "o")
+    assert_parity(lse, lse_ref, TOL_F32 if dtype == torch.float32 else 1e-3, "lse")
+    # the backward kernel on its own: it is handed the oracle's stored output and log-sum-exp, so both
+    # sides start from identical inputs (forward -> backward chains are covered at section level)
+    o_in = torch.tensor(o_ref.reshape(n, -1), dtype=dtype, device="cuda")
+    lse_in = torch.tensor(lse_ref, dtype=torch.float32, device="cuda")
     dq, dk, dv = attention_bwd(f64(d_o).reshape(n, nq, hd), q, k, v, cu, causal, o=o_ref)
     ref = np.concatenate([dq.reshape(n, -1), dk.reshape(n, -1), dv.reshape(n, -1)], axis=1)
-    dqkv = B.k_attention_backward(qkv, o, lse, d_o, batch, nq, nkv, hd, causal)
+    dqkv = B.k_attention_backward(qkv, o_in, lse_in, d_o, batch, nq, nkv, hd, causal)
     for name, sl in [("dq", slice(0, nq * hd)), ("dk", slice(nq * hd, (nq + nkv) * hd)), ("dv", slice((nq + nkv) * hd, None))]:
         assert_parity(dqkv[:, sl], rnd(ref[:, sl]), tol, name)

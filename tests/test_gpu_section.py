@@ -4,7 +4,7 @@ import numpy as np
 import pytest
 import torch
 
-from oracle import identity, round_bf16
+from oracle import identity, round_bf16, round_f32
 from oracle.kd import kd_loss_forward_backward as oracle_kd
 from oracle.section import SectionSpec, section_backward, section_forward
 from oracle.step import distill_step
@@ -55,7 +55,7 @@ def run_distill(work, seed, chunk=None, tol=None, tol_loss=None, tol_wgrad=None)
                                      d_w_student=d_ws)
     torch.cuda.synchronize()
     ref = distill_step(spec_of(t_cfg), wl.to_f64(tw), spec_of(s_cfg), wl.to_f64(sw), cu, ids.cpu().numpy(),
-                       wl.to_f64(wt), wl.to_f64(ws), kd.temperature, 1.0 / n, rnd)
+                       wl.to_f64(wt), wl.to_f64(ws), kd.temperature, 1.0 / n, rnd, rnd_res=round_f32 if bf else None)
     check = assert_parity_chain if bf else assert_parity
     check(h_t, ref["h_t"], tol, "h_teacher")
     check(out["h_out"], ref["h_s"], tol, "h_student")
@@ -119,7 +119,7 @@ def test_c4_reduced_encoder_forward_backward():
     lengths = [0, 300, 0, 257, 64, 0]                       # text-only samples contribute nothing
     w, x, d_h, cu, grads, out = run_encoder(cfg, 0, lengths)
     spec = spec_of(cfg)
-    h, cache = section_forward(spec, wl.to_f64(w), cu, wl.to_f64(x), round_bf16, keep=True)
+    h, cache = section_forward(spec, wl.to_f64(w), cu, wl.to_f64(x), round_bf16, keep=True, rnd_res=round_f32)
     g_ref, dx_ref = section_backward(spec, wl.to_f64(w), cu, cache, wl.to_f64(d_h), round_bf16)
     assert_parity_chain(out["h_out"], h, TOL_BF16, "h_out")
     assert_parity_chain(out["d_x_in"], dx_ref, TOL_BF16, "d_x_in")

@@ -33,6 +33,17 @@ def test_brute_force_tiny(rng, causal):
     assert np.allclose(attention_fwd(q, k, v, cu, causal), _brute(q, k, v, cu, causal), atol=1e-13)
 
 
+def test_log_sum_exp_against_loops(rng):
+    cu = [0, 3, 7]
+    q, k, v = rng.standard_normal((7, 2, 4)), rng.standard_normal((7, 1, 4)), rng.standard_normal((7, 1, 4))
+    _, lse = attention_fwd(q, k, v, cu, True, return_lse=True)
+    for b in range(2):
+        for i in range(cu[b], cu[b + 1]):
+            for h in range(2):
+                tot = sum(math.exp(sum(q[i, h, d] * k[j, 0, d] for d in range(4)) / 2.0) for j in range(cu[b], i + 1))
+                assert lse[h, i] == pytest.approx(math.log(tot), rel=1e-12)
+
+
 def test_length_one_and_equal_keys(rng):
     q, k, v = rng.standard_normal((1, 2, 8)), rng.standard_normal((1, 2, 8)), rng.standard_normal((1, 2, 8))
     assert np.allclose(attention_fwd(q, k, v, [0, 1], True), v)
