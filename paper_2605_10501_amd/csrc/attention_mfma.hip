@@ -1,4 +1,4 @@
-// Matrix-core variable-length attention for bf16 (head_dim 64, 80, 128), forward.
+// Matrix-core variable-length attention for bf16 (head_dim 64, 80, 128), forward and backward.
 //
 // One workgroup (4 waves) owns 128 consecutive queries of one sequence and one query head; each
 // wave owns 32 of them and keeps its Q fragments in registers.  Keys / values are visited 64 at a
@@ -185,6 +185,323 @@ __global__ __launch_bounds__(256) void attn_fwd_mfma_kernel(const bf16_t *__rest
     if (half == 0) lse[(long)h * n + q] = (m + log2f(l)) * 0.6931471805599453f;
 }
 
+
+// ===================================================================== backward
+// delta[h, t] = sum_d dO[t, h, d] O[t, h, d]  (the row term of the softmax Jacobian)
+__global__ __launch_bounds__(256) void attn_delta_kernel(const bf16_t *__restrict__ o, const bf16_t *__restrict__ d_o,
+                                                          float *__restrict__ delta, int n, int nq, int hd) {
+    const long idx = (long)blockIdx.x * blockDim.x + threadIdx.x;
+    if (idx >= (long)n * nq) return;
+    const long t = idx / nq;
+    const int h = idx % nq;
+    const bf16_t *a = o + idx * hd, *b = d_o + idx * hd;
+    float acc = 0.f;
+    for (int d = 0; d < hd; d += 8) {
+        const Vec16<bf16_t> x = ldv(a + d), y = ldv(b + d);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) acc += (float)x.v[e] * (float)y.v[e];
+    }
+    delta[(long)h * n + t] = acc;
+}
+
+// 8 k-slots of a transposed tile T[row][64]: columns c0 + 4h + {0..3} and c0 + 8 + 4h + {0..3}
+__device__ __forceinline__ bf16x8 load_tr_frag(const bf16_t *tile, int row, int chunk, int half) {
+    const uint2 lo = *(const uint2 *)(tile + lds_off(row, chunk) + 4 * half);
+    const uint2 hi = *(const uint2 *)(tile + lds_off(row, chunk + 1) + 4 * half);
+    union { uint4 u; bf16x8 v; } f;
+    f.u = make_uint4(lo.x, lo.y, hi.x, hi.y);
+    return f.v;
+}
+
+// dQ: same decomposition as the forward kernel (workgroup = 128 queries of one head, keys visited
+// 64 at a time).  S^T = K Q^T and dP^T = V dO^T are accumulator tiles with one query per lane, so
+// P = exp2(S^T c - lse[q]) and dS^T = P (dP^T - delta[q]) use per-lane scalars, and dS^T is the B
+// operand of dQ^T += Kt dS^T with Kt the K tile transposed while staged.
+template <int HD, bool CAUSAL>
+__global__ __launch_bounds__(256) void attn_bwd_dq_mfma_kernel(const bf16_t *__restrict__ qkv, const bf16_t *__restrict__ d_o,
+                                                                const float *__restrict__ lse, const float *__restrict__ delta,
+                                                                bf16_t *__restrict__ dqkv, const int *__restrict__ cu, int n,
+                                                                int nq, int nkv, float scale) {
+    using D = AttnDims<HD>;
+    constexpr int BQ = 128, BKV = 64;
+    constexpr int RM = D::NKS * 64 * 64, TR = D::DB * 32 * 64, BUF = 2 * RM + TR;
+    extern __shared__ __align__(16) unsigned char smem_raw[];
+    bf16_t *sm = (bf16_t *)smem_raw;  // [2][K row-major | V row-major | K transposed]
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int lrow = lane & 31, half = lane >> 5;
+    const int b = blockIdx.z, h = blockIdx.y;
+    const int s0 = cu[b], s1 = cu[b + 1];
+    const int ntile = (s1 - s0 + BQ - 1) / BQ;
+    const int qt = ntile - 1 - (int)blockIdx.x;
+    if (qt < 0) return;
+    const int g = h / (nq / nkv);
+    const long ld = (long)(nq + 2 * nkv) * HD;
+    const int q0 = s0 + qt * BQ + wave * 32;
+    const int kv_end = CAUSAL ? (s0 + (qt + 1) * BQ < s1 ? s0 + (qt + 1) * BQ : s1) : s1;
+    const int nkt = (kv_end - s0 + BKV - 1) / BKV;
+    const bf16_t *Kb = qkv + (long)(nq + g) * HD;
+    const bf16_t *Vb = qkv + (long)(nq + nkv + g) * HD;
+    const float c = scale * 1.4426950408889634f;
+
+    const int q = q0 + lrow;
+    const bool qok = q < s1;
+    bf16x8 qf[D::KST], dof[D::KST];
+    {
+        const bf16_t *qp = qkv + (long)q * ld + (long)h * HD + half * 8;
+        const bf16_t *dp = d_o + (long)q * nq * HD + (long)h * HD + half * 8;
+#pragma unroll
+        for (int ks = 0; ks < D::KST; ++ks) {
+            if (qok) {
+                qf[ks] = *(const bf16x8 *)(qp + ks * 16);
+                dof[ks] = *(const bf16x8 *)(dp + ks * 16);
+            } else {
+#pragma unroll
+                for (int i = 0; i < 8; ++i) { qf[ks][i] = (bf16_t)0.f; dof[ks][i] = (bf16_t)0.f; }
+            }
+        }
+    }
+    const float lse2 = qok ? lse[(long)h * n + q] * 1.4426950408889634f : 0.f;
+    const float dlt = qok ? delta[(long)h * n + q] : 0.f;
+
+    Stager<64, false> sk[D::NKS], sv[D::NKS];
+    Stager<D::DB * 32, true> skt;
+    auto load_tile = [&](int j) {
+#pragma unroll
+        for (int i = 0; i < D::NKS; ++i) {
+            sk[i].load(Kb, ld, s0 + j * BKV, kv_end, i * 64, HD, tid);
+            sv[i].load(Vb, ld, s0 + j * BKV, kv_end, i * 64, HD, tid);
+        }
+        skt.load(Kb, ld, 0, HD, s0 + j * BKV, kv_end, tid);
+    };
+    auto store_tile = [&](int buf) {
+        bf16_t *base = sm + buf * BUF;
+#pragma unroll
+        for (int i = 0; i < D::NKS; ++i) {
+            sk[i].store(base + i * 64 * 64, tid);
+            sv[i].store(base + RM + i * 64 * 64, tid);
+        }
+        skt.store(base + 2 * RM, tid);
+    };
+
+    f32x16 dq[D::DB];
+#pragma unroll
+    for (int i = 0; i < D::DB; ++i)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) dq[i][r] = 0.f;
+
+    load_tile(0);
+    store_tile(0);
+    __syncthreads();
+
+    for (int j = 0; j < nkt; ++j) {
+        const int cur = j & 1;
+        if (j + 1 < nkt) load_tile(j + 1);
+        const bf16_t *kt = sm + cur * BUF, *vt = kt + RM, *ktt = kt + 2 * RM;
+        const int key0 = s0 + j * BKV + 4 * half;
+#pragma unroll
+        for (int kb = 0; kb < 2; ++kb) {
+            f32x16 st, dp;
+#pragma unroll
+            for (int r = 0; r < 16; ++r) { st[r] = 0.f; dp[r] = 0.f; }
+#pragma unroll
+            for (int ks = 0; ks < D::KST; ++ks) {
+                const int off = (ks / 4) * 64 * 64 + lds_off(kb * 32 + lrow, (ks % 4) * 2 + half);
+                st = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*(const bf16x8 *)(kt + off), qf[ks], st, 0, 0, 0);
+                dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*(const bf16x8 *)(vt + off), dof[ks], dp, 0, 0, 0);
+            }
+            float ds[16];
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int key = key0 + kb * 32 + 8 * (r >> 2) + (r & 3);
+                const bool ok = qok && key < kv_end && (!CAUSAL || key <= q);
+                const float p = ok ? __builtin_amdgcn_exp2f(st[r] * c - lse2) : 0.f;
+                ds[r] = p * (dp[r] - dlt);
+            }
+#pragma unroll
+            for (int t = 0; t < 2; ++t) {
+                const bf16x8 dsf = pack8(&ds[8 * t]);
+#pragma unroll
+                for (int db = 0; db < D::DB; ++db)
+                    dq[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(load_tr_frag(ktt, db * 32 + lrow, kb * 4 + 2 * t, half),
+                                                                       dsf, dq[db], 0, 0, 0);
+            }
+        }
+        if (j + 1 < nkt) store_tile(cur ^ 1);
+        __syncthreads();
+    }
+    if (!qok) return;
+    bf16_t *op = dqkv + (long)q * ld + (long)h * HD;
+#pragma unroll
+    for (int db = 0; db < D::DB; ++db)
+#pragma unroll
+        for (int rg = 0; rg < 4; ++rg) {
+            const int d = db * 32 + 8 * rg + 4 * half;
+            if (d < HD) {
+                union { uint2 u; bf16_t v[4]; } w;
+#pragma unroll
+                for (int e = 0; e < 4; ++e) w.v[e] = (bf16_t)(dq[db][rg * 4 + e] * scale);
+                *(uint2 *)(op + d) = w.u;
+            }
+        }
+}
+
+// dK, dV: workgroup = 128 keys of one KV head (32 per wave, K and V fragments in registers); it
+// walks the query heads of the group and their query tiles (64 rows at a time through LDS, both
+// row-major and transposed).  S = Q K^T and dP = dO V^T are accumulator tiles with one KEY per
+// lane and queries down the registers, which is the A-operand layout of dV += P^T dO and
+// dK += dS^T Q.  The sums over the query group stay in registers: no atomics.
+template <int HD, bool CAUSAL>
+__global__ __launch_bounds__(256) void attn_bwd_dkv_mfma_kernel(const bf16_t *__restrict__ qkv, const bf16_t *__restrict__ d_o,
+                                                                 const float *__restrict__ lse, const float *__restrict__ delta,
+                                                                 bf16_t *__restrict__ dqkv, const int *__restrict__ cu, int n,
+                                                                 int nq, int nkv, float scale) {
+    using D = AttnDims<HD>;
+    constexpr int BK_ = 128, BQ = 64;
+    constexpr int RM = D::NKS * 64 * 64, TR = D::DB * 32 * 64, BUF = 2 * RM + 2 * TR;
+    extern __shared__ __align__(16) unsigned char smem_raw[];
+    bf16_t *sm = (bf16_t *)smem_raw;           // [2][Q rm | dO rm | Q^T | dO^T]
+    float *sf = (float *)(sm + 2 * BUF);       // [2][lse2[64] | delta[64]]
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int lrow = lane & 31, half = lane >> 5;
+    const int b = blockIdx.z, g = blockIdx.y;
+    const int s0 = cu[b], s1 = cu[b + 1];
+    const int kblk = blockIdx.x * BK_;                      // first key of the workgroup, relative to s0
+    if (kblk >= s1 - s0) return;
+    const int grp = nq / nkv;
+    const long ld = (long)(nq + 2 * nkv) * HD;
+    const int key = s0 + kblk + wave * 32 + lrow;           // this lane's key (token index)
+    const bool kok = key < s1;
+    const float c = scale * 1.4426950408889634f;
+
+    bf16x8 kf[D::KST], vf[D::KST];
+    {
+        const bf16_t *kp = qkv + (long)key * ld + (long)(nq + g) * HD + half * 8;
+        const bf16_t *vp = qkv + (long)key * ld + (long)(nq + nkv + g) * HD + half * 8;
+#pragma unroll
+        for (int ks = 0; ks < D::KST; ++ks) {
+            if (kok) {
+                kf[ks] = *(const bf16x8 *)(kp + ks * 16);
+                vf[ks] = *(const bf16x8 *)(vp + ks * 16);
+            } else {
+#pragma unroll
+                for (int i = 0; i < 8; ++i) { kf[ks][i] = (bf16_t)0.f; vf[ks][i] = (bf16_t)0.f; }
+            }
+        }
+    }
+    // query tiles that see this key block
+    const int qt_first = CAUSAL ? kblk / BQ : 0;
+    const int nqt = (s1 - s0 + BQ - 1) / BQ - qt_first;
+    const int niter = nqt * grp;
+
+    Stager<64, false> sq[D::NKS], sdo[D::NKS];
+    Stager<D::DB * 32, true> sqt, sdot;
+    float r_lse = 0.f, r_dlt = 0.f;
+    auto load_tile = [&](int it) {
+        const int h = g * grp + it / nqt;
+        const int qs = s0 + (qt_first + it % nqt) * BQ;
+        const bf16_t *Qb = qkv + (long)h * HD;
+        const bf16_t *Ob = d_o + (long)h * HD;
+#pragma unroll
+        for (int i = 0; i < D::NKS; ++i) {
+            sq[i].load(Qb, ld, qs, s1, i * 64, HD, tid);
+            sdo[i].load(Ob, (long)nq * HD, qs, s1, i * 64, HD, tid);
+        }
+        sqt.load(Qb, ld, 0, HD, qs, s1, tid);
+        sdot.load(Ob, (long)nq * HD, 0, HD, qs, s1, tid);
+        if (tid < 64) r_lse = qs + tid < s1 ? lse[(long)h * n + qs + tid] * 1.4426950408889634f : 0.f;
+        else if (tid < 128) r_dlt = qs + tid - 64 < s1 ? delta[(long)h * n + qs + tid - 64] : 0.f;
+    };
+    auto store_tile = [&](int buf) {
+        bf16_t *base = sm + buf * BUF;
+#pragma unroll
+        for (int i = 0; i < D::NKS; ++i) {
+            sq[i].store(base + i * 64 * 64, tid);
+            sdo[i].store(base + RM + i * 64 * 64, tid);
+        }
+        sqt.store(base + 2 * RM, tid);
+        sdot.store(base + 2 * RM + TR, tid);
+        if (tid < 64) sf[buf * 128 + tid] = r_lse;
+        else if (tid < 128) sf[buf * 128 + tid] = r_dlt;
+    };
+
+    f32x16 dk[D::DB], dv[D::DB];
+#pragma unroll
+    for (int i = 0; i < D::DB; ++i)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) { dk[i][r] = 0.f; dv[i][r] = 0.f; }
+
+    if (niter > 0) {
+        load_tile(0);
+        store_tile(0);
+    }
+    __syncthreads();
+
+    for (int it = 0; it < niter; ++it) {
+        const int cur = it & 1;
+        if (it + 1 < niter) load_tile(it + 1);
+        const bf16_t *qt_ = sm + cur * BUF, *dot_ = qt_ + RM, *qtt = qt_ + 2 * RM, *dott = qtt + TR;
+        const float *ls = sf + cur * 128, *dl = ls + 64;
+        const int qs = s0 + (qt_first + it % nqt) * BQ;
+#pragma unroll
+        for (int qb = 0; qb < 2; ++qb) {
+            f32x16 st, dp;
+#pragma unroll
+            for (int r = 0; r < 16; ++r) { st[r] = 0.f; dp[r] = 0.f; }
+#pragma unroll
+            for (int ks = 0; ks < D::KST; ++ks) {
+                const int off = (ks / 4) * 64 * 64 + lds_off(qb * 32 + lrow, (ks % 4) * 2 + half);
+                st = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*(const bf16x8 *)(qt_ + off), kf[ks], st, 0, 0, 0);
+                dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*(const bf16x8 *)(dot_ + off), vf[ks], dp, 0, 0, 0);
+            }
+            // accumulator rows are queries qb*32 + 8*(r/4) + 4*half + r%4, the column is this lane's key
+            float p[16], ds[16];
+#pragma unroll
+            for (int rg = 0; rg < 4; ++rg) {
+                const int qr = qb * 32 + 8 * rg + 4 * half;
+                const float4 l4 = *(const float4 *)(ls + qr), d4 = *(const float4 *)(dl + qr);
+                const float lv[4] = {l4.x, l4.y, l4.z, l4.w}, dvv[4] = {d4.x, d4.y, d4.z, d4.w};
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    const int r = rg * 4 + e;
+                    const int qq = qs + qr + e;
+                    const bool ok = kok && qq < s1 && (!CAUSAL || key <= qq);
+                    p[r] = ok ? __builtin_amdgcn_exp2f(st[r] * c - lv[e]) : 0.f;
+                    ds[r] = p[r] * (dp[r] - dvv[e]);
+                }
+            }
+#pragma unroll
+            for (int t = 0; t < 2; ++t) {
+                const bf16x8 pf = pack8(&p[8 * t]), dsf = pack8(&ds[8 * t]);
+#pragma unroll
+                for (int db = 0; db < D::DB; ++db) {
+                    dv[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(pf, load_tr_frag(dott, db * 32 + lrow, qb * 4 + 2 * t, half), dv[db], 0, 0, 0);
+                    dk[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(dsf, load_tr_frag(qtt, db * 32 + lrow, qb * 4 + 2 * t, half), dk[db], 0, 0, 0);
+                }
+            }
+        }
+        if (it + 1 < niter) store_tile(cur ^ 1);
+        __syncthreads();
+    }
+
+    // accumulators: row = key wave*32 + 8*(r/4) + 4*half + r%4, column d = db*32 + lrow
+    bf16_t *dkp = dqkv + (long)(nq + g) * HD, *dvp = dqkv + (long)(nq + nkv + g) * HD;
+#pragma unroll
+    for (int db = 0; db < D::DB; ++db) {
+        const int d = db * 32 + lrow;
+        if (d >= HD) continue;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            const int kk = s0 + kblk + wave * 32 + 8 * (r >> 2) + 4 * half + (r & 3);
+            if (kk < s1) {
+                dkp[(long)kk * ld + d] = (bf16_t)(dk[db][r] * scale);
+                dvp[(long)kk * ld + d] = (bf16_t)dv[db][r];
+            }
+        }
+    }
+}
+
 template <int HD>
 ms_status launch_fwd(int causal, int nq, int nkv, int n, int n_seqs, int max_seqlen, const int *cu, const void *qkv,
                      void *o, float *lse, hipStream_t s) {
@@ -208,10 +525,44 @@ ms_status launch_fwd(int causal, int nq, int nkv, int n, int n_seqs, int max_seq
     return MS_OK;
 }
 
+
+template <int HD>
+ms_status launch_bwd(int causal, int nq, int nkv, int n, int n_seqs, int max_seqlen, const int *cu, const void *qkv,
+                     const void *o, const float *lse, const void *d_o, void *dqkv, void *scratch, hipStream_t s) {
+    using D = AttnDims<HD>;
+    float *delta = (float *)scratch;
+    attn_delta_kernel<<<ms_cdiv((long)n * nq, 256), 256, 0, s>>>((const bf16_t *)o, (const bf16_t *)d_o, delta, n, nq, HD);
+    MS_LAUNCH_CHECK();
+    const float scale = 1.f / sqrtf((float)HD);
+    const size_t smem_dq = (size_t)2 * (2 * D::NKS * 64 * 64 + D::DB * 32 * 64) * sizeof(bf16_t);
+    const size_t smem_dkv = (size_t)2 * (2 * D::NKS * 64 * 64 + 2 * D::DB * 32 * 64) * sizeof(bf16_t) + 2 * 128 * sizeof(float);
+    dim3 grid_dq(ms_cdiv(max_seqlen, 128), nq, n_seqs), grid_dkv(ms_cdiv(max_seqlen, 128), nkv, n_seqs);
+#define GO(C)                                                                                                          \
+    do {                                                                                                               \
+        static bool attr_set = false;                                                                                  \
+        if (!attr_set) {                                                                                               \
+            MS_CHECK_HIP(hipFuncSetAttribute((const void *)attn_bwd_dq_mfma_kernel<HD, C>,                             \
+                                             hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem_dq));               \
+            MS_CHECK_HIP(hipFuncSetAttribute((const void *)attn_bwd_dkv_mfma_kernel<HD, C>,                            \
+                                             hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem_dkv));              \
+            attr_set = true;                                                                                           \
+        }                                                                                                              \
+        attn_bwd_dq_mfma_kernel<HD, C><<<grid_dq, 256, smem_dq, s>>>((const bf16_t *)qkv, (const bf16_t *)d_o, lse,    \
+                                                                      delta, (bf16_t *)dqkv, cu, n, nq, nkv, scale);   \
+        MS_LAUNCH_CHECK();                                                                                             \
+        attn_bwd_dkv_mfma_kernel<HD, C><<<grid_dkv, 256, smem_dkv, s>>>((const bf16_t *)qkv, (const bf16_t *)d_o, lse, \
+                                                                         delta, (bf16_t *)dqkv, cu, n, nq, nkv, scale);\
+    } while (0)
+    if (causal) GO(true); else GO(false);
+#undef GO
+    MS_LAUNCH_CHECK();
+    return MS_OK;
+}
+
 }  // namespace
 
 bool attn_mfma_forward_supported(int hd) { return hd == 64 || hd == 80 || hd == 128; }
-bool attn_mfma_backward_supported(int) { return false; }
+bool attn_mfma_backward_supported(int hd) { return hd == 64 || hd == 80 || hd == 128; }
 
 ms_status attn_mfma_forward(int causal, int nq, int nkv, int hd, int n, int n_seqs, int max_seqlen, const int *cu,
                             const void *qkv, void *o, float *lse, hipStream_t s) {
@@ -222,8 +573,14 @@ ms_status attn_mfma_forward(int causal, int nq, int nkv, int hd, int n, int n_se
     return ms_fail(MS_ERR_UNSUPPORTED, "attention: head_dim %d has no matrix-core kernel", hd);
 }
 
-size_t attn_mfma_backward_scratch_bytes(int, int, int, int) { return 0; }
-ms_status attn_mfma_backward(int, int, int, int, int, int, int, const int *, const void *, const void *, const float *,
-                             const void *, void *, void *, hipStream_t) {
-    return ms_fail(MS_ERR_UNSUPPORTED, "attention backward: matrix-core path not built");
+size_t attn_mfma_backward_scratch_bytes(int nq, int, int, int n) { return ms_align_up((size_t)nq * n * sizeof(float)); }
+
+ms_status attn_mfma_backward(int causal, int nq, int nkv, int hd, int n, int n_seqs, int max_seqlen, const int *cu,
+                             const void *qkv, const void *o, const float *lse, const void *d_o, void *dqkv,
+                             void *scratch, hipStream_t s) {
+    if (max_seqlen <= 0) return MS_OK;
+    if (hd == 64) return launch_bwd<64>(causal, nq, nkv, n, n_seqs, max_seqlen, cu, qkv, o, lse, d_o, dqkv, scratch, s);
+    if (hd == 80) return launch_bwd<80>(causal, nq, nkv, n, n_seqs, max_seqlen, cu, qkv, o, lse, d_o, dqkv, scratch, s);
+    if (hd == 128) return launch_bwd<128>(causal, nq, nkv, n, n_seqs, max_seqlen, cu, qkv, o, lse, d_o, dqkv, scratch, s);
+    return ms_fail(MS_ERR_UNSUPPORTED, "attention backward: head_dim %d has no matrix-core kernel", hd);
 }
