@@ -5,8 +5,8 @@
 //   * both operands are staged global -> registers -> LDS with a one-tile register prefetch and
 //     two LDS buffers, so one barrier per K tile is enough;
 //   * LDS rows are 64 bf16 (128 B) = eight 16-byte chunks; chunk c of row r is stored at chunk
-//     c ^ ((r ^ (r >> 3)) & 7), which keeps the fragment reads (32 consecutive rows, one chunk)
-//     and the transposed staging writes (rows 8 apart) off each other's banks;
+//     c ^ (r & 7) ^ ((r >> 3) & 3), which spreads the fragment reads (32 consecutive rows, one
+//     chunk) over the banks;
 //   * an operand stored K-major ("transposed": weight gradients, input gradients) is
 //     transposed in registers while it is staged: a thread loads an 8(k) x 8(m) block as eight
 //     16-byte rows and writes eight 16-byte K-contiguous rows, so the MFMA loop is the same for
@@ -14,6 +14,8 @@
 //   * workgroup ids are remapped so that the ids one XCD receives (id mod 8) are neighbours in
 //     tile space and share operand panels in that XCD's L2.
 // fp32: a plain LDS-tiled FMA kernel (correctness path of the fp32 workload).
+#include <stdlib.h>
+
 #include "common.h"
 #include "launch.h"
 #include "mfma_tiles.h"
@@ -90,25 +92,25 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmParams p) {
             sa.load(A, p.lda, m0, p.M, (kt_begin + kt + 1) * BK, k_end, tid);
             sb.load(B, p.ldb, n0, p.N, (kt_begin + kt + 1) * BK, k_end, tid);
         }
+        // fragments of k-step kk+1 are fetched from LDS while the MFMAs of k-step kk run
+        bf16x8 af[2][MI], bfr[2][NI];
+        auto load_frags = [&](int kk, int slot) {
+#pragma unroll
+            for (int i = 0; i < MI; ++i)
+                af[slot][i] = *(const bf16x8 *)(As + cur * BM * BK + lds_off(wm * WTM + i * 32 + frow, kk * 2 + fhalf));
+#pragma unroll
+            for (int j = 0; j < NI; ++j)
+                bfr[slot][j] = *(const bf16x8 *)(Bs + cur * BN * BK + lds_off(wn * WTN + j * 32 + frow, kk * 2 + fhalf));
+        };
+        load_frags(0, 0);
 #pragma unroll
         for (int kk = 0; kk < BK / 16; ++kk) {
-            bf16x8 af[MI], bfr[NI];
-#pragma unroll
-            for (int i = 0; i < MI; ++i) {
-                const int r = i * 32 + frow;
-                // the swizzle uses the row index inside the whole tile
-                af[i] = *(const bf16x8 *)(As + cur * BM * BK + lds_off(wm * WTM + r, kk * 2 + fhalf));
-            }
-#pragma unroll
-            for (int j = 0; j < NI; ++j) {
-                const int r = j * 32 + frow;
-                bfr[j] = *(const bf16x8 *)(Bs + cur * BN * BK + lds_off(wn * WTN + r, kk * 2 + fhalf));
-            }
+            if (kk + 1 < BK / 16) load_frags(kk + 1, (kk + 1) & 1);
 #pragma unroll
             for (int i = 0; i < MI; ++i)
 #pragma unroll
                 for (int j = 0; j < NI; ++j)
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bfr[j], acc[i][j], 0, 0, 0);
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[kk & 1][i], bfr[kk & 1][j], acc[i][j], 0, 0, 0);
         }
         if (kt + 1 < nk) {
             sa.store(As + (cur ^ 1) * BM * BK, tid);
@@ -143,6 +145,188 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmParams p) {
                 }
             }
         }
+}
+
+// ------------------------------------------------------------------ fast path
+// Same tiling and MFMA loop, but
+//   * an operand stored K-contiguous goes global -> LDS directly (buffer_load ... lds, 16 bytes per
+//     lane, one instruction fills 8 tile rows = 1 KB): lane l of the instruction that fills rows
+//     8G .. 8G+7 lands at row 8G + l/8, chunk position l%8, so it fetches the chunk that the LDS
+//     swizzle assigns to that position.  No staging registers, no LDS store instructions; rows
+//     past the end of the matrix read as zero through the buffer descriptor's range check;
+//   * the epilogue addresses C (and the residual) through buffer descriptors as well, so rows
+//     past M are dropped by the range check and columns past N by one select per column:
+//     no per-element branches.
+// Needs K % 64 == 0 when an operand is K-contiguous and every matrix below 4 GB.
+typedef __attribute__((address_space(3))) void lds_void;
+constexpr unsigned kOob = 0xFFFFF000u;   // byte offset beyond any descriptor range
+
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void *p, long bytes) {
+    return __builtin_amdgcn_make_buffer_rsrc(const_cast<void *>(p), 0, (int)(unsigned)bytes, 0x00020000);
+}
+
+template <int ROWS, int NWAVES>
+struct DmaStager {
+    static constexpr int NI = ROWS / 8 / NWAVES;   // instructions per wave per tile
+    unsigned rowoff;                       // byte offset of this lane's row within an 8-row group
+    unsigned ld8;                          // bytes between 8-row groups
+    int x;                                 // (lane & 7) ^ (lane >> 3): chunk swizzle without the group term (g & 3)
+    __device__ __forceinline__ void init(long ld, int row0, int lane) {
+        rowoff = (unsigned)(((long)(row0 + (lane >> 3)) * ld) * 2);
+        ld8 = (unsigned)(ld * 16);
+        x = (lane & 7) ^ (lane >> 3);
+    }
+    // wave (scalar) fills 8-row groups wave*NI .. wave*NI + NI-1 of the tile
+    // valid == false fills the tile with zeros (every lane out of range)
+    __device__ __forceinline__ void issue(__amdgpu_buffer_rsrc_t rs, bf16_t *tile, int k0, int wave, bool valid) const {
+#pragma unroll
+        for (int i = 0; i < NI; ++i) {
+            const int g = wave * NI + i;
+            const unsigned voff = valid ? rowoff + g * ld8 + ((x ^ (g & 3)) << 4) : kOob;
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(rs, (lds_void *)(tile + g * 8 * BK), 16, voff, k0 * 2, 0, 0);
+        }
+    }
+};
+
+template <int BM, int BN, int WM, int WN, bool TA, bool TB>
+__global__ __launch_bounds__(64 * WM * WN) void gemm_bf16_fast_kernel(GemmParams p) {
+    constexpr int NT = 64 * WM * WN;
+    constexpr int WTM = BM / WM, WTN = BN / WN, MI = WTM / 32, NI = WTN / 32;
+    // four separate LDS objects (not one carved array): the compiler orders LDS reads against
+    // in-flight direct-to-LDS loads by alias analysis, and can only tell the buffer being filled
+    // from the buffer being read when they are distinct objects
+    __shared__ __align__(16) bf16_t As0[BM * BK], As1[BM * BK], Bs0[BN * BK], Bs1[BN * BK];
+
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform: keep it in a scalar register
+    const int wm = wave / WN, wn = wave % WN;
+    int pid;
+    {
+        const int nb = gridDim.x, b = blockIdx.x;
+        const int per = nb >> 3, rem = nb & 7, x = b & 7, q = b >> 3;
+        pid = x * per + (x < rem ? x : rem) + q;
+    }
+    constexpr int GM = BM >= 256 ? 4 : 8;
+    const int group = pid / (GM * p.tiles_n);
+    const int first_m = group * GM;
+    const int gsize = (p.tiles_m - first_m) < GM ? (p.tiles_m - first_m) : GM;
+    const int tm = first_m + (pid % (GM * p.tiles_n)) % gsize;
+    const int tn = (pid % (GM * p.tiles_n)) / gsize;
+    const int m0 = tm * BM, n0 = tn * BN;
+
+    const int kt_begin = blockIdx.y * p.k_tiles_per_split;
+    int kt_end = kt_begin + p.k_tiles_per_split;
+    const int kt_total = (p.K + BK - 1) / BK;
+    if (kt_end > kt_total) kt_end = kt_total;
+    const int nk = kt_end - kt_begin;
+    if (nk <= 0) return;
+
+    const bf16_t *A = (const bf16_t *)p.A, *B = (const bf16_t *)p.B;
+    Stager<BM, true, NT> sa;          // used only when TA
+    Stager<BN, true, NT> sb;          // used only when TB
+    DmaStager<BM, WM * WN> da;        // used only when !TA
+    DmaStager<BN, WM * WN> db;
+    const __amdgpu_buffer_rsrc_t ra = make_rsrc(A, (long)p.M * p.lda * 2), rb = make_rsrc(B, (long)p.N * p.ldb * 2);
+    if constexpr (!TA) da.init(p.lda, m0, lane);
+    if constexpr (!TB) db.init(p.ldb, n0, lane);
+
+    f32x16 acc[MI][NI];
+#pragma unroll
+    for (int i = 0; i < MI; ++i)
+#pragma unroll
+        for (int j = 0; j < NI; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+
+    // start moving K tile kt towards LDS; a tile past the end of this workgroup's K range arrives as zeros
+    auto fetch = [&](int kt, bf16_t *as, bf16_t *bs) {
+        const bool valid = kt < nk;
+        const int k0 = (kt_begin + kt) * BK;
+        const int k_end = valid ? p.K : 0;
+        if constexpr (TA) sa.load(A, p.lda, m0, p.M, k0, k_end, tid); else da.issue(ra, as, k0, wave, valid);
+        if constexpr (TB) sb.load(B, p.ldb, n0, p.N, k0, k_end, tid); else db.issue(rb, bs, k0, wave, valid);
+    };
+    auto commit = [&](bf16_t *as, bf16_t *bs) {          // register-staged operands: write them to LDS
+        if constexpr (TA) sa.store(as, tid);
+        if constexpr (TB) sb.store(bs, tid);
+    };
+    const int frow = lane & 31, fhalf = lane >> 5;
+    auto compute = [&](const bf16_t *as, const bf16_t *bs) {
+        bf16x8 af[2][MI], bfr[2][NI];
+        auto load_frags = [&](int kk, int slot) {
+#pragma unroll
+            for (int i = 0; i < MI; ++i)
+                af[slot][i] = *(const bf16x8 *)(as + lds_off(wm * WTM + i * 32 + frow, kk * 2 + fhalf));
+#pragma unroll
+            for (int j = 0; j < NI; ++j)
+                bfr[slot][j] = *(const bf16x8 *)(bs + lds_off(wn * WTN + j * 32 + frow, kk * 2 + fhalf));
+        };
+        load_frags(0, 0);
+#pragma unroll
+        for (int kk = 0; kk < BK / 16; ++kk) {
+            if (kk + 1 < BK / 16) load_frags(kk + 1, (kk + 1) & 1);
+#pragma unroll
+            for (int i = 0; i < MI; ++i)
+#pragma unroll
+                for (int j = 0; j < NI; ++j)
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[kk & 1][i], bfr[kk & 1][j], acc[i][j], 0, 0, 0);
+        }
+    };
+
+    fetch(0, As0, Bs0);
+    commit(As0, Bs0);
+    __syncthreads();
+    // two K tiles per trip so that each half names its LDS buffers statically; an odd tile count is
+    // rounded up with a tile of zeros (a single loop exit keeps the accumulators in place)
+    for (int kt = 0; kt < nk; kt += 2) {
+        fetch(kt + 1, As1, Bs1);
+        compute(As0, Bs0);
+        commit(As1, Bs1);
+        __syncthreads();
+        if (kt + 2 < nk) fetch(kt + 2, As0, Bs0);
+        compute(As1, Bs1);
+        if (kt + 2 < nk) commit(As0, Bs0);
+        __syncthreads();
+    }
+
+    // epilogue through buffer descriptors: offsets past the range are dropped (stores) or read 0
+    const int esz = p.c_fp32 ? 4 : 2;
+    const __amdgpu_buffer_rsrc_t rc = make_rsrc(p.C, (long)p.M * p.ldc * esz);
+    const int rsz = p.res_fp32 ? 4 : 2;
+    const __amdgpu_buffer_rsrc_t rr = make_rsrc(p.residual ? p.residual : p.C, p.residual ? (long)p.M * p.ldr * rsz : 0);
+    const bf16_t *bias = (const bf16_t *)p.bias;
+#pragma unroll
+    for (int j = 0; j < NI; ++j) {
+        const int col = n0 + wn * WTN + j * 32 + frow;
+        const bool cok = col < p.N;
+        const float bv = (bias && cok) ? (float)bias[col] : 0.f;
+#pragma unroll
+        for (int i = 0; i < MI; ++i) {
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int row = m0 + wm * WTM + i * 32 + 8 * (r >> 2) + 4 * fhalf + (r & 3);
+                float v = acc[i][j][r] * p.alpha + bv;
+                if (p.residual) {
+                    const unsigned ro = cok ? (unsigned)(((long)row * p.ldr + col) * rsz) : kOob;
+                    if (p.res_fp32) v += __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(rr, ro, 0, 0));
+                    else v += (float)__builtin_bit_cast(bf16_t, __builtin_amdgcn_raw_buffer_load_b16(rr, ro, 0, 0));
+                }
+                const unsigned co = cok ? (unsigned)(((long)row * p.ldc + col) * esz) : kOob;
+                if (p.c_fp32) {
+                    if (p.atomic) {
+                        if (cok && row < p.M) unsafeAtomicAdd((float *)p.C + (long)row * p.ldc + col, v);
+                    } else {
+                        if (p.accumulate) v += __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(rc, co, 0, 0));
+                        __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(unsigned, v), rc, co, 0, 0);
+                    }
+                } else {
+                    __builtin_amdgcn_raw_buffer_store_b16(__builtin_bit_cast(unsigned short, (bf16_t)v), rc, co, 0, 0);
+                }
+            }
+            // keep the scheduler from pulling every accumulator out of the AGPRs at once
+            __builtin_amdgcn_sched_barrier(0);
+        }
+    }
 }
 
 // ------------------------------------------------------------------ fp32 reference-speed kernel
@@ -194,6 +378,20 @@ __global__ __launch_bounds__(256) void gemm_f32_kernel(GemmF32Params p) {
             float *c = p.C + (long)row * p.ldc + col;
             *c = p.accumulate ? *c + v : v;
         }
+}
+
+template <int BM, int BN, int WM, int WN>
+ms_status launch_bf16_fast(const GemmParams &p, int ta, int tb, int splits, hipStream_t s) {
+    dim3 grid(p.tiles_m * p.tiles_n, splits);
+    ProfScope ps((ta || tb) ? 1 : 0, 2.0 * p.M * p.N * p.K, s);
+#define GO(TA, TB) gemm_bf16_fast_kernel<BM, BN, WM, WN, TA, TB><<<grid, 64 * WM * WN, 0, s>>>(p)
+    if (!ta && !tb) GO(false, false);
+    else if (!ta && tb) GO(false, true);
+    else if (ta && !tb) GO(true, false);
+    else GO(true, true);
+#undef GO
+    MS_LAUNCH_CHECK();
+    return MS_OK;
 }
 
 template <int BM, int BN>
@@ -251,7 +449,21 @@ extern "C" ms_status ms_k_gemm(int32_t dtype, int32_t trans_a, int32_t trans_b, 
     p.A = A; p.B = B; p.C = C; p.bias = bias; p.residual = residual;
     p.lda = lda; p.ldb = ldb; p.ldc = ldc; p.ldr = ldr; p.M = M; p.N = N; p.K = K; p.alpha = alpha;
     p.c_fp32 = c_fp32; p.accumulate = accumulate; p.res_fp32 = residual_fp32;
-    constexpr int BM = 128, BN = 128;
+    // fast path (direct-to-LDS loads, descriptor-addressed epilogue) needs full K tiles for a K-contiguous
+    // operand and 32-bit byte offsets; tile 256 x 256 when that still gives every CU work, else 128 x 128
+    static const int forced = [] { const char *e = getenv("MS_GEMM_TILE"); return e ? atoi(e) : 0; }();
+    const long lim = (1L << 32) - (1L << 20);
+    const long rows_a = trans_a ? K : M, rows_b = trans_b ? K : N;
+    const bool fast = forced >= 0 && ((trans_a && trans_b) || K % BK == 0) && (rows_a + 256) * lda * 2 < lim &&
+                      (rows_b + 256) * ldb * 2 < lim && ((long)M + 256) * ldc * 4 < lim &&
+                      (!residual || ((long)M + 256) * ldr * 4 < lim);
+    // 256 x 256 (8 waves, one workgroup per CU) runs ~1.25x the rate of 128 x 128 (4 waves, two per CU) when the
+    // grid fills whole rounds of CUs: pick by estimated rate x last-round occupancy
+    const long tiles256 = (long)ms_cdiv(M, 256) * ms_cdiv(N, 256), tiles128 = (long)ms_cdiv(M, 128) * ms_cdiv(N, 128);
+    const double eff256 = (double)tiles256 / (double)(ms_cdiv(tiles256, 256) * 256L);
+    const double eff128 = (double)tiles128 / (double)(ms_cdiv(tiles128, 512) * 512L);
+    const bool big = fast && (forced > 0 ? forced == 256 : (tiles256 >= 192 && 1.25 * eff256 > eff128));
+    const int BM = big ? 256 : 128, BN = BM;
     p.tiles_m = ms_cdiv(M, BM); p.tiles_n = ms_cdiv(N, BN);
     const int kt_total = ms_cdiv(K, BK) < 1 ? 1 : ms_cdiv(K, BK);
     int splits = split_k;
@@ -267,5 +479,7 @@ extern "C" ms_status ms_k_gemm(int32_t dtype, int32_t trans_a, int32_t trans_b, 
     p.k_tiles_per_split = ms_cdiv(kt_total, splits);
     splits = ms_cdiv(kt_total, p.k_tiles_per_split);
     p.atomic = splits > 1;
-    return launch_bf16<BM, BN>(p, trans_a, trans_b, splits, s);
+    if (big) return launch_bf16_fast<256, 256, 2, 4>(p, trans_a, trans_b, splits, s);
+    if (fast) return launch_bf16_fast<128, 128, 2, 2>(p, trans_a, trans_b, splits, s);
+    return launch_bf16<128, 128>(p, trans_a, trans_b, splits, s);
 }

@@ -1,7 +1,8 @@
 // LDS tile helpers shared by the matrix-core kernels (GEMM and attention).
 //
 // A tile is [rows][64] bf16: 128-byte rows of eight 16-byte chunks, chunk c of row r stored at
-// chunk c ^ ((r ^ (r >> 3)) & 7).  Stager moves one such tile global -> registers -> LDS; for an
+// chunk c ^ swz(r), swz(r) = (r & 7) ^ ((r >> 3) & 3).  Only row bits 0..4 enter the swizzle, so rows
+// 32 apart use the same chunk order and fragment addresses differ by compile-time constants.  Stager moves one such tile global -> registers -> LDS; for an
 // operand whose 64-wide dimension is the strided one in memory it transposes 8 x 8 blocks in
 // registers on the way.
 #pragma once
@@ -9,7 +10,7 @@
 
 constexpr int BK = 64;
 
-__device__ __forceinline__ int swz(int r, int c) { return c ^ ((r ^ (r >> 3)) & 7); }
+__device__ __forceinline__ int swz(int r, int c) { return c ^ ((r & 7) ^ ((r >> 3) & 3)); }
 
 // element offset (in bf16) of 16-byte chunk c of row r in a [rows][64] tile
 __device__ __forceinline__ int lds_off(int r, int c) { return r * BK + swz(r, c) * 8; }
@@ -18,9 +19,11 @@ __device__ __forceinline__ uint32_t pack_lo(uint32_t a, uint32_t b) { return (a 
 __device__ __forceinline__ uint32_t pack_hi(uint32_t a, uint32_t b) { return (a >> 16) | (b & 0xffff0000u); }
 
 // Staging of one operand tile of ROWS x 64 (rows = m or n index, 64 = k).
-template <int ROWS, bool TRANS>
+template <int ROWS, bool TRANS, int NT = 256>
 struct Stager {
-    static constexpr int NREG = TRANS ? 8 * ((ROWS + 255) / 256) : ROWS / 32;
+    static constexpr int NB = (ROWS + NT - 1) / NT;          // 8 x 8 blocks per thread (transposed)
+    static constexpr int RPP = NT / 8;                      // rows per pass (row-major)
+    static constexpr int NREG = TRANS ? 8 * NB : ROWS / RPP;
     uint4 reg[NREG];
 
     // P: base pointer; ld: leading dimension; row0: first m/n of the tile; rows_total: M or N;
@@ -31,16 +34,15 @@ struct Stager {
             const int k = k0 + c * 8;
 #pragma unroll
             for (int i = 0; i < NREG; ++i) {
-                const int r = row0 + r0 + 32 * i;
+                const int r = row0 + r0 + RPP * i;
                 if (r < rows_total && k < k_end) reg[i] = *(const uint4 *)(P + (long)r * ld + k);
                 else reg[i] = make_uint4(0, 0, 0, 0);
             }
         } else {
-            constexpr int MB = ROWS / 8;  // 8-row blocks along m
 #pragma unroll
-            for (int b = 0; b < (ROWS + 255) / 256; ++b) {
-                const int blk = tid + 256 * b;
-                const int mb = blk % MB, kb = blk / MB;
+            for (int b = 0; b < NB; ++b) {
+                const int blk = tid + NT * b;   // 8 x 8 block: k-block fastest, then m-block
+                const int kb = blk & 7, mb = blk >> 3;
                 const int m = row0 + mb * 8;
 #pragma unroll
                 for (int j = 0; j < 8; ++j) {
@@ -57,16 +59,15 @@ struct Stager {
             const int c = tid & 7, r0 = tid >> 3;
 #pragma unroll
             for (int i = 0; i < NREG; ++i) {
-                const int r = r0 + 32 * i;
+                const int r = r0 + RPP * i;
                 *(uint4 *)(tile + lds_off(r, c)) = reg[i];
             }
         } else {
-            constexpr int MB = ROWS / 8;
 #pragma unroll
-            for (int b = 0; b < (ROWS + 255) / 256; ++b) {
-                const int blk = tid + 256 * b;
+            for (int b = 0; b < NB; ++b) {
+                const int blk = tid + NT * b;
                 if (blk < ROWS) {
-                    const int mb = blk % MB, kb = blk / MB;
+                    const int kb = blk & 7, mb = blk >> 3;
                     const uint4 *in = &reg[b * 8];
                     // in[j] = 8 m-values at k = j; out row i = 8 k-values at m = i
 #pragma unroll
