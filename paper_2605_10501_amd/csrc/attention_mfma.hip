@@ -29,32 +29,57 @@ __device__ __forceinline__ bf16x8 pack8(const float *v) {
     return r;
 }
 
+// One direct-to-LDS instruction of a row-major tile [64 rows][HD] kept as NKS sub-tiles [64][64]:
+// instruction idx fills 8-row group idx % 8 of sub-tile idx / 8 from rows row0.. of a matrix with
+// leading dimension ld (elements), starting at column col0.  Columns past HD arrive as zeros.
+template <int HD>
+__device__ __forceinline__ void attn_dma(__amdgpu_buffer_rsrc_t rs, bf16_t *tile, int row0, long ld, int col0, int idx,
+                                         int lane) {
+    const int sub = idx >> 3, g = idx & 7;
+    const int r = g * 8 + (lane >> 3);
+    const int c = (lane & 7) ^ (lane >> 3) ^ (g & 3);
+    const int d = sub * 64 + c * 8;
+    const unsigned voff = d < HD ? (unsigned)(((long)(row0 + r) * ld + col0 + d) * 2) : kOob;
+    __builtin_amdgcn_raw_ptr_buffer_load_lds(rs, (lds_void *)(tile + sub * 4096 + g * 512), 16, voff, 0, 0, 0);
+}
+
+// A-operand fragment (rows = 32 consecutive columns m of the tile starting at m0, k-slots = tile
+// rows k0 + 4h + {0..3} and k0 + 8 + 4h + {0..3}) of a row-major tile [64][HD], read transposed.
+__device__ __forceinline__ bf16x8 attn_tr_frag(const bf16_t *tile, int k0, int m0, int lane) {
+    const int h = lane >> 5, dg = (lane >> 4) & 1, r = lane & 15;
+    const int row = k0 + 4 * h + (r >> 2);
+    const int m = m0 + 16 * dg + 4 * (r & 3);
+    const bf16_t *base = tile + (m >> 6) * 4096 + (m & 7);
+    const int chunk = (m & 63) >> 3;
+    return tr_frag(base + lds_off(row, chunk), base + lds_off(row + 8, chunk));
+}
+
 template <int HD, bool CAUSAL>
 __global__ __launch_bounds__(256) void attn_fwd_mfma_kernel(const bf16_t *__restrict__ qkv, bf16_t *__restrict__ o,
                                                              float *__restrict__ lse, const int *__restrict__ cu, int n,
-                                                             int nq, int nkv, float scale_log2e) {
+                                                             int nq, int nkv, int n_seqs, int ntile_max, float scale_log2e) {
     using D = AttnDims<HD>;
-    constexpr int BQ = 128, BKV = 64;
-    extern __shared__ __align__(16) unsigned char smem_raw[];
-    bf16_t *Ks = (bf16_t *)smem_raw;                          // [2][NKS][64 * 64]
-    bf16_t *Vt = Ks + 2 * D::NKS * 64 * 64;                   // [2][DB * 32 * 64]
+    constexpr int BQ = 128, BKV = 64, TS = D::NKS * 4096;
+    // separate LDS objects per buffer: lets the compiler tell in-flight direct-to-LDS loads from reads
+    __shared__ __align__(16) bf16_t K0[TS], K1[TS], V0[TS], V1[TS];
 
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int lrow = lane & 31, half = lane >> 5;
-    const int b = blockIdx.z, h = blockIdx.y;
+    // heaviest (latest) query tiles of all heads and sequences first
+    const int per = nq * n_seqs;
+    const int qt = ntile_max - 1 - (int)(blockIdx.x / per);
+    const int h = (blockIdx.x % per) % nq, b = (blockIdx.x % per) / nq;
     const int s0 = cu[b], s1 = cu[b + 1];
-    const int ntile = (s1 - s0 + BQ - 1) / BQ;
-    const int qt = ntile - 1 - (int)blockIdx.x;               // long (late) tiles first
-    if (qt < 0) return;
+    if (qt * BQ >= s1 - s0) return;
     const int g = h / (nq / nkv);
     const long ld = (long)(nq + 2 * nkv) * HD;
-    const int q0 = s0 + qt * BQ + wave * 32;                  // first query of this wave (token index)
+    const int q0 = s0 + qt * BQ + wave * 32;
     const int kv_end = CAUSAL ? (s0 + (qt + 1) * BQ < s1 ? s0 + (qt + 1) * BQ : s1) : s1;
     const int nkt = (kv_end - s0 + BKV - 1) / BKV;
-    const bf16_t *Kb = qkv + (long)(nq + g) * HD;
-    const bf16_t *Vb = qkv + (long)(nq + nkv + g) * HD;
+    const int kcol = (nq + g) * HD, vcol = (nq + nkv + g) * HD;
+    const __amdgpu_buffer_rsrc_t rs = make_rsrc(qkv, (long)n * ld * 2);
 
-    // Q fragments (B operand): lane = query column, 8 consecutive d per k-step half
     bf16x8 qf[D::KST];
     {
         const int q = q0 + lrow;
@@ -67,18 +92,15 @@ __global__ __launch_bounds__(256) void attn_fwd_mfma_kernel(const bf16_t *__rest
                 for (int i = 0; i < 8; ++i) qf[ks][i] = (bf16_t)0.f;
         }
     }
-
-    Stager<64, false> sk[D::NKS];
-    Stager<D::DB * 32, true> sv;
-    auto load_tile = [&](int j) {
+    // each wave issues a quarter of the 2 * 8 * NKS instructions that fill one K tile and one V tile
+    auto issue = [&](int j, bf16_t *kt, bf16_t *vt) {
+        constexpr int PER = 4 * D::NKS;
 #pragma unroll
-        for (int i = 0; i < D::NKS; ++i) sk[i].load(Kb, ld, s0 + j * BKV, kv_end, i * 64, HD, tid);
-        sv.load(Vb, ld, 0, HD, s0 + j * BKV, kv_end, tid);
-    };
-    auto store_tile = [&](int buf) {
-#pragma unroll
-        for (int i = 0; i < D::NKS; ++i) sk[i].store(Ks + (buf * D::NKS + i) * 64 * 64, tid);
-        sv.store(Vt + buf * D::DB * 32 * 64, tid);
+        for (int i = 0; i < PER; ++i) {
+            const int idx = wave * PER + i;
+            if (idx < 8 * D::NKS) attn_dma<HD>(rs, kt, s0 + j * BKV, ld, kcol, idx, lane);
+            else attn_dma<HD>(rs, vt, s0 + j * BKV, ld, vcol, idx - 8 * D::NKS, lane);
+        }
     };
 
     f32x16 oacc[D::DB];
@@ -87,17 +109,9 @@ __global__ __launch_bounds__(256) void attn_fwd_mfma_kernel(const bf16_t *__rest
 #pragma unroll
         for (int r = 0; r < 16; ++r) oacc[i][r] = 0.f;
     float m = -INFINITY, l = 0.f;
+    const int q = q0 + lrow;
 
-    load_tile(0);
-    store_tile(0);
-    __syncthreads();
-
-    for (int j = 0; j < nkt; ++j) {
-        const int cur = j & 1;
-        if (j + 1 < nkt) load_tile(j + 1);
-        const bf16_t *kt = Ks + cur * D::NKS * 64 * 64;
-        const bf16_t *vt = Vt + cur * D::DB * 32 * 64;
-
+    auto compute = [&](int j, const bf16_t *kt, const bf16_t *vt) {
         // S^T[key][q] for the 64 keys of the tile: two 32-key blocks
         f32x16 st[2];
 #pragma unroll
@@ -106,12 +120,11 @@ __global__ __launch_bounds__(256) void attn_fwd_mfma_kernel(const bf16_t *__rest
             for (int r = 0; r < 16; ++r) st[kb][r] = 0.f;
 #pragma unroll
             for (int ks = 0; ks < D::KST; ++ks) {
-                const bf16x8 kf = *(const bf16x8 *)(kt + (ks / 4) * 64 * 64 + lds_off(kb * 32 + lrow, (ks % 4) * 2 + half));
+                const bf16x8 kf = *(const bf16x8 *)(kt + (ks / 4) * 4096 + lds_off(kb * 32 + lrow, (ks % 4) * 2 + half));
                 st[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[ks], st[kb], 0, 0, 0);
             }
         }
         // scale, mask, row maximum (one query per lane; the other half-wave holds the other keys)
-        const int q = q0 + lrow;
         const int key0 = s0 + j * BKV + 4 * half;
         float p[2][16];
         float mx = -INFINITY;
@@ -139,34 +152,39 @@ __global__ __launch_bounds__(256) void attn_fwd_mfma_kernel(const bf16_t *__rest
             }
         l = l * alpha + psum;
         m = m_new;
+        if (__builtin_amdgcn_ballot_w64(alpha != 1.f)) {    // wave-uniform: skip the rescale once the maxima settle
 #pragma unroll
-        for (int i = 0; i < D::DB; ++i)
+            for (int i = 0; i < D::DB; ++i)
 #pragma unroll
-            for (int r = 0; r < 16; ++r) oacc[i][r] *= alpha;
-
-        // O^T[d][q] += Vt[d][key] P^T[key][q]; k-slot s of half h is key 16t + 4h + s (s < 4),
-        // 16t + 8 + 4h + (s - 4) (s >= 4): exactly accumulator registers 8t .. 8t+7
+                for (int r = 0; r < 16; ++r) oacc[i][r] *= alpha;
+        }
+        // O^T[d][q] += V^T[d][key] P^T[key][q]; k-slot s of half h is key 16t + 4h + s (s < 4),
+        // 16t + 8 + 4h + (s - 4) (s >= 4): exactly accumulator registers 8t .. 8t+7.  V stays
+        // row-major in LDS and is read through the transposing LDS load.
 #pragma unroll
         for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
             for (int t = 0; t < 2; ++t) {
                 const bf16x8 pf = pack8(&p[kb][8 * t]);
 #pragma unroll
-                for (int db = 0; db < D::DB; ++db) {
-                    const int row = db * 32 + lrow;
-                    const uint2 lo = *(const uint2 *)(vt + lds_off(row, kb * 4 + 2 * t) + 4 * half);
-                    const uint2 hi = *(const uint2 *)(vt + lds_off(row, kb * 4 + 2 * t + 1) + 4 * half);
-                    union { uint4 u; bf16x8 v; } vf;
-                    vf.u = make_uint4(lo.x, lo.y, hi.x, hi.y);
-                    oacc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf.v, pf, oacc[db], 0, 0, 0);
-                }
+                for (int db = 0; db < D::DB; ++db)
+                    oacc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(attn_tr_frag(vt, kb * 32 + 16 * t, db * 32, lane), pf,
+                                                                         oacc[db], 0, 0, 0);
             }
-        if (j + 1 < nkt) store_tile(cur ^ 1);
+    };
+
+    issue(0, K0, V0);
+    __syncthreads();
+    for (int j = 0; j < nkt; j += 2) {
+        if (j + 1 < nkt) issue(j + 1, K1, V1);
+        compute(j, K0, V0);
+        __syncthreads();
+        if (j + 2 < nkt) issue(j + 2, K0, V0);
+        if (j + 1 < nkt) compute(j + 1, K1, V1);
         __syncthreads();
     }
 
     l += __shfl_xor(l, 32, 64);
-    const int q = q0 + lrow;
     if (q >= s1) return;
     const float inv = 1.f / l;
     bf16_t *op = o + (long)q * nq * HD + (long)h * HD;
@@ -184,7 +202,6 @@ __global__ __launch_bounds__(256) void attn_fwd_mfma_kernel(const bf16_t *__rest
         }
     if (half == 0) lse[(long)h * n + q] = (m + log2f(l)) * 0.6931471805599453f;
 }
-
 
 // ===================================================================== backward
 // delta[h, t] = sum_d dO[t, h, d] O[t, h, d]  (the row term of the softmax Jacobian)
@@ -505,26 +522,16 @@ __global__ __launch_bounds__(256) void attn_bwd_dkv_mfma_kernel(const bf16_t *__
 template <int HD>
 ms_status launch_fwd(int causal, int nq, int nkv, int n, int n_seqs, int max_seqlen, const int *cu, const void *qkv,
                      void *o, float *lse, hipStream_t s) {
-    using D = AttnDims<HD>;
-    const size_t smem = (size_t)2 * (D::NKS * 64 * 64 + D::DB * 32 * 64) * sizeof(bf16_t);
-    dim3 grid(ms_cdiv(max_seqlen, 128), nq, n_seqs);
+    const int ntile_max = ms_cdiv(max_seqlen, 128);
+    const long blocks = (long)ntile_max * nq * n_seqs;
+    if (blocks > 0x7fffffffL || (long)n * (nq + 2 * nkv) * HD * 2 >= (1L << 32) - (1L << 20))
+        return ms_fail(MS_ERR_UNSUPPORTED, "attention: batch too large for 32-bit tile offsets");
     const float sc = 1.4426950408889634f / sqrtf((float)HD);
-#define GO(C)                                                                                                   \
-    do {                                                                                                        \
-        static bool attr_set = false;                                                                           \
-        if (!attr_set && smem > 48 * 1024) {                                                                    \
-            MS_CHECK_HIP(hipFuncSetAttribute((const void *)attn_fwd_mfma_kernel<HD, C>,                         \
-                                             hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem));           \
-            attr_set = true;                                                                                    \
-        }                                                                                                       \
-        attn_fwd_mfma_kernel<HD, C><<<grid, 256, smem, s>>>((const bf16_t *)qkv, (bf16_t *)o, lse, cu, n, nq, nkv, sc); \
-    } while (0)
-    if (causal) GO(true); else GO(false);
-#undef GO
+    if (causal) attn_fwd_mfma_kernel<HD, true><<<(unsigned)blocks, 256, 0, s>>>((const bf16_t *)qkv, (bf16_t *)o, lse, cu, n, nq, nkv, n_seqs, ntile_max, sc);
+    else attn_fwd_mfma_kernel<HD, false><<<(unsigned)blocks, 256, 0, s>>>((const bf16_t *)qkv, (bf16_t *)o, lse, cu, n, nq, nkv, n_seqs, ntile_max, sc);
     MS_LAUNCH_CHECK();
     return MS_OK;
 }
-
 
 template <int HD>
 ms_status launch_bwd(int causal, int nq, int nkv, int n, int n_seqs, int max_seqlen, const int *cu, const void *qkv,

@@ -158,13 +158,6 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmParams p) {
 //     past M are dropped by the range check and columns past N by one select per column:
 //     no per-element branches.
 // Needs K % 64 == 0 when an operand is K-contiguous and every matrix below 4 GB.
-typedef __attribute__((address_space(3))) void lds_void;
-constexpr unsigned kOob = 0xFFFFF000u;   // byte offset beyond any descriptor range
-
-__device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void *p, long bytes) {
-    return __builtin_amdgcn_make_buffer_rsrc(const_cast<void *>(p), 0, (int)(unsigned)bytes, 0x00020000);
-}
-
 template <int ROWS, int NWAVES>
 struct DmaStager {
     static constexpr int NI = ROWS / 8 / NWAVES;   // instructions per wave per tile

@@ -15,6 +15,29 @@ __device__ __forceinline__ int swz(int r, int c) { return c ^ ((r & 7) ^ ((r >> 
 // element offset (in bf16) of 16-byte chunk c of row r in a [rows][64] tile
 __device__ __forceinline__ int lds_off(int r, int c) { return r * BK + swz(r, c) * 8; }
 
+// ---- direct global -> LDS loads through a buffer descriptor ----------------------------------
+// buffer_load_dwordx4 ... lds: lane l of the wave writes its 16 bytes at (LDS base) + 16 l; a lane
+// whose byte offset is outside the descriptor's range writes zeros.
+typedef __attribute__((address_space(3))) void lds_void;
+constexpr unsigned kOob = 0xFFFFF000u;   // byte offset beyond any descriptor range
+
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void *p, long bytes) {
+    return __builtin_amdgcn_make_buffer_rsrc(const_cast<void *>(p), 0, (int)(unsigned)bytes, 0x00020000);
+}
+
+// ---- transposing LDS read (ds_read_b64_tr_b16) --------------------------------------------------
+// Within each group of 16 lanes, lane r supplies the address of an 8-byte row (4 bf16); lane i
+// receives element i%4 of rows i/4, 4 + i/4, 8 + i/4, 12 + i/4.  With a tile stored [k][m]
+// (m contiguous) and lane r pointing at T[k0 + r/4][m0 + 4 (r%4)], lane i therefore receives
+// T[k0 .. k0+3][m0 + i]: four consecutive k of its own column, i.e. MFMA operand slots.
+typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4;
+typedef __attribute__((address_space(3))) bf16x4 lds_bf16x4;
+__device__ __forceinline__ bf16x8 tr_frag(const bf16_t *p0, const bf16_t *p1) {
+    const bf16x4 a = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_bf16x4 *)p0);
+    const bf16x4 b = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_bf16x4 *)p1);
+    return __builtin_shufflevector(a, b, 0, 1, 2, 3, 4, 5, 6, 7);
+}
+
 __device__ __forceinline__ uint32_t pack_lo(uint32_t a, uint32_t b) { return (a & 0xffffu) | (b << 16); }
 __device__ __forceinline__ uint32_t pack_hi(uint32_t a, uint32_t b) { return (a >> 16) | (b & 0xffff0000u); }
 
