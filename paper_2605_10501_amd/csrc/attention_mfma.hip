@@ -2,10 +2,9 @@
 //
 // One workgroup (4 waves) owns 128 consecutive queries of one sequence and one query head; each
 // wave owns 32 of them and keeps its Q fragments in registers.  Keys / values are visited 64 at a
-// time through two LDS buffers (global -> registers -> LDS, one barrier per tile):
-//   * K tile row-major [64 keys][head_dim] as 64-wide sub-tiles;
-//   * V tile transposed while staged, Vt[head_dim][64 keys], so that the P V product can contract
-//     over keys with 8-byte LDS reads.
+// time through two LDS buffers filled by direct global -> LDS loads (no staging registers), both
+// row-major [64 keys][head_dim] as 64-wide swizzled sub-tiles; the P V product, which contracts
+// over keys, reads V through the transposing LDS load (ds_read_b64_tr_b16).
 // Scores are computed transposed, S^T = K Q^T (v_mfma_f32_32x32x16_bf16): in the accumulator
 // layout a lane then holds 32 keys of ONE query, so the online-softmax row maximum and sum are
 // register reductions plus a single cross-half shuffle, the rescale factor is a per-lane scalar,
@@ -221,44 +220,35 @@ __global__ __launch_bounds__(256) void attn_delta_kernel(const bf16_t *__restric
     delta[(long)h * n + t] = acc;
 }
 
-// 8 k-slots of a transposed tile T[row][64]: columns c0 + 4h + {0..3} and c0 + 8 + 4h + {0..3}
-__device__ __forceinline__ bf16x8 load_tr_frag(const bf16_t *tile, int row, int chunk, int half) {
-    const uint2 lo = *(const uint2 *)(tile + lds_off(row, chunk) + 4 * half);
-    const uint2 hi = *(const uint2 *)(tile + lds_off(row, chunk + 1) + 4 * half);
-    union { uint4 u; bf16x8 v; } f;
-    f.u = make_uint4(lo.x, lo.y, hi.x, hi.y);
-    return f.v;
-}
-
 // dQ: same decomposition as the forward kernel (workgroup = 128 queries of one head, keys visited
-// 64 at a time).  S^T = K Q^T and dP^T = V dO^T are accumulator tiles with one query per lane, so
-// P = exp2(S^T c - lse[q]) and dS^T = P (dP^T - delta[q]) use per-lane scalars, and dS^T is the B
-// operand of dQ^T += Kt dS^T with Kt the K tile transposed while staged.
+// 64 at a time, K and V tiles loaded directly into LDS).  S^T = K Q^T and dP^T = V dO^T are
+// accumulator tiles with one query per lane, so P = exp2(S^T c - lse[q]) and
+// dS^T = P (dP^T - delta[q]) use per-lane scalars, and dS^T is the B operand of dQ^T += K^T dS^T
+// with K^T read from the row-major K tile through the transposing LDS load.
 template <int HD, bool CAUSAL>
 __global__ __launch_bounds__(256) void attn_bwd_dq_mfma_kernel(const bf16_t *__restrict__ qkv, const bf16_t *__restrict__ d_o,
                                                                 const float *__restrict__ lse, const float *__restrict__ delta,
                                                                 bf16_t *__restrict__ dqkv, const int *__restrict__ cu, int n,
-                                                                int nq, int nkv, float scale) {
+                                                                int nq, int nkv, int n_seqs, int ntile_max, float scale) {
     using D = AttnDims<HD>;
-    constexpr int BQ = 128, BKV = 64;
-    constexpr int RM = D::NKS * 64 * 64, TR = D::DB * 32 * 64, BUF = 2 * RM + TR;
-    extern __shared__ __align__(16) unsigned char smem_raw[];
-    bf16_t *sm = (bf16_t *)smem_raw;  // [2][K row-major | V row-major | K transposed]
+    constexpr int BQ = 128, BKV = 64, TS = D::NKS * 4096;
+    __shared__ __align__(16) bf16_t K0[TS], K1[TS], V0[TS], V1[TS];
 
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int lrow = lane & 31, half = lane >> 5;
-    const int b = blockIdx.z, h = blockIdx.y;
+    const int per = nq * n_seqs;
+    const int qt = ntile_max - 1 - (int)(blockIdx.x / per);
+    const int h = (blockIdx.x % per) % nq, b = (blockIdx.x % per) / nq;
     const int s0 = cu[b], s1 = cu[b + 1];
-    const int ntile = (s1 - s0 + BQ - 1) / BQ;
-    const int qt = ntile - 1 - (int)blockIdx.x;
-    if (qt < 0) return;
+    if (qt * BQ >= s1 - s0) return;
     const int g = h / (nq / nkv);
     const long ld = (long)(nq + 2 * nkv) * HD;
     const int q0 = s0 + qt * BQ + wave * 32;
     const int kv_end = CAUSAL ? (s0 + (qt + 1) * BQ < s1 ? s0 + (qt + 1) * BQ : s1) : s1;
     const int nkt = (kv_end - s0 + BKV - 1) / BKV;
-    const bf16_t *Kb = qkv + (long)(nq + g) * HD;
-    const bf16_t *Vb = qkv + (long)(nq + nkv + g) * HD;
+    const int kcol = (nq + g) * HD, vcol = (nq + nkv + g) * HD;
+    const __amdgpu_buffer_rsrc_t rs = make_rsrc(qkv, (long)n * ld * 2);
     const float c = scale * 1.4426950408889634f;
 
     const int q = q0 + lrow;
@@ -281,24 +271,14 @@ __global__ __launch_bounds__(256) void attn_bwd_dq_mfma_kernel(const bf16_t *__r
     const float lse2 = qok ? lse[(long)h * n + q] * 1.4426950408889634f : 0.f;
     const float dlt = qok ? delta[(long)h * n + q] : 0.f;
 
-    Stager<64, false> sk[D::NKS], sv[D::NKS];
-    Stager<D::DB * 32, true> skt;
-    auto load_tile = [&](int j) {
+    auto issue = [&](int j, bf16_t *kt, bf16_t *vt) {
+        constexpr int PER = 4 * D::NKS;
 #pragma unroll
-        for (int i = 0; i < D::NKS; ++i) {
-            sk[i].load(Kb, ld, s0 + j * BKV, kv_end, i * 64, HD, tid);
-            sv[i].load(Vb, ld, s0 + j * BKV, kv_end, i * 64, HD, tid);
+        for (int i = 0; i < PER; ++i) {
+            const int idx = wave * PER + i;
+            if (idx < 8 * D::NKS) attn_dma<HD>(rs, kt, s0 + j * BKV, ld, kcol, idx, lane);
+            else attn_dma<HD>(rs, vt, s0 + j * BKV, ld, vcol, idx - 8 * D::NKS, lane);
         }
-        skt.load(Kb, ld, 0, HD, s0 + j * BKV, kv_end, tid);
-    };
-    auto store_tile = [&](int buf) {
-        bf16_t *base = sm + buf * BUF;
-#pragma unroll
-        for (int i = 0; i < D::NKS; ++i) {
-            sk[i].store(base + i * 64 * 64, tid);
-            sv[i].store(base + RM + i * 64 * 64, tid);
-        }
-        skt.store(base + 2 * RM, tid);
     };
 
     f32x16 dq[D::DB];
@@ -307,14 +287,7 @@ __global__ __launch_bounds__(256) void attn_bwd_dq_mfma_kernel(const bf16_t *__r
 #pragma unroll
         for (int r = 0; r < 16; ++r) dq[i][r] = 0.f;
 
-    load_tile(0);
-    store_tile(0);
-    __syncthreads();
-
-    for (int j = 0; j < nkt; ++j) {
-        const int cur = j & 1;
-        if (j + 1 < nkt) load_tile(j + 1);
-        const bf16_t *kt = sm + cur * BUF, *vt = kt + RM, *ktt = kt + 2 * RM;
+    auto compute = [&](int j, const bf16_t *kt, const bf16_t *vt) {
         const int key0 = s0 + j * BKV + 4 * half;
 #pragma unroll
         for (int kb = 0; kb < 2; ++kb) {
@@ -323,7 +296,7 @@ __global__ __launch_bounds__(256) void attn_bwd_dq_mfma_kernel(const bf16_t *__r
             for (int r = 0; r < 16; ++r) { st[r] = 0.f; dp[r] = 0.f; }
 #pragma unroll
             for (int ks = 0; ks < D::KST; ++ks) {
-                const int off = (ks / 4) * 64 * 64 + lds_off(kb * 32 + lrow, (ks % 4) * 2 + half);
+                const int off = (ks / 4) * 4096 + lds_off(kb * 32 + lrow, (ks % 4) * 2 + half);
                 st = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*(const bf16x8 *)(kt + off), qf[ks], st, 0, 0, 0);
                 dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*(const bf16x8 *)(vt + off), dof[ks], dp, 0, 0, 0);
             }
@@ -340,11 +313,20 @@ __global__ __launch_bounds__(256) void attn_bwd_dq_mfma_kernel(const bf16_t *__r
                 const bf16x8 dsf = pack8(&ds[8 * t]);
 #pragma unroll
                 for (int db = 0; db < D::DB; ++db)
-                    dq[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(load_tr_frag(ktt, db * 32 + lrow, kb * 4 + 2 * t, half),
-                                                                       dsf, dq[db], 0, 0, 0);
+                    dq[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(attn_tr_frag(kt, kb * 32 + 16 * t, db * 32, lane), dsf,
+                                                                       dq[db], 0, 0, 0);
             }
         }
-        if (j + 1 < nkt) store_tile(cur ^ 1);
+    };
+
+    issue(0, K0, V0);
+    __syncthreads();
+    for (int j = 0; j < nkt; j += 2) {
+        if (j + 1 < nkt) issue(j + 1, K1, V1);
+        compute(j, K0, V0);
+        __syncthreads();
+        if (j + 2 < nkt) issue(j + 2, K0, V0);
+        if (j + 1 < nkt) compute(j + 1, K1, V1);
         __syncthreads();
     }
     if (!qok) return;
@@ -364,33 +346,37 @@ __global__ __launch_bounds__(256) void attn_bwd_dq_mfma_kernel(const bf16_t *__r
 }
 
 // dK, dV: workgroup = 128 keys of one KV head (32 per wave, K and V fragments in registers); it
-// walks the query heads of the group and their query tiles (64 rows at a time through LDS, both
-// row-major and transposed).  S = Q K^T and dP = dO V^T are accumulator tiles with one KEY per
-// lane and queries down the registers, which is the A-operand layout of dV += P^T dO and
-// dK += dS^T Q.  The sums over the query group stay in registers: no atomics.
+// walks the query heads of the group and their query tiles, 64 rows at a time, with the Q and dO
+// tiles loaded directly into LDS.  S = Q K^T and dP = dO V^T are accumulator tiles with one KEY
+// per lane and queries down the registers, which is the A-operand layout of dV += P^T dO and
+// dK += dS^T Q; their B operands (dO and Q with queries as the contraction index) come from the
+// row-major tiles through the transposing LDS load.  The sums over the query group stay in
+// registers: no atomics.
 template <int HD, bool CAUSAL>
 __global__ __launch_bounds__(256) void attn_bwd_dkv_mfma_kernel(const bf16_t *__restrict__ qkv, const bf16_t *__restrict__ d_o,
                                                                  const float *__restrict__ lse, const float *__restrict__ delta,
                                                                  bf16_t *__restrict__ dqkv, const int *__restrict__ cu, int n,
-                                                                 int nq, int nkv, float scale) {
+                                                                 int nq, int nkv, int n_seqs, float scale) {
     using D = AttnDims<HD>;
-    constexpr int BK_ = 128, BQ = 64;
-    constexpr int RM = D::NKS * 64 * 64, TR = D::DB * 32 * 64, BUF = 2 * RM + 2 * TR;
-    extern __shared__ __align__(16) unsigned char smem_raw[];
-    bf16_t *sm = (bf16_t *)smem_raw;           // [2][Q rm | dO rm | Q^T | dO^T]
-    float *sf = (float *)(sm + 2 * BUF);       // [2][lse2[64] | delta[64]]
+    constexpr int BK_ = 128, BQ = 64, TS = D::NKS * 4096;
+    __shared__ __align__(16) bf16_t Q0[TS], Q1[TS], O0[TS], O1[TS];
+    __shared__ __align__(16) float F0[128], F1[128];       // per query row: lse * log2(e) | delta
 
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int lrow = lane & 31, half = lane >> 5;
-    const int b = blockIdx.z, g = blockIdx.y;
+    // earliest key blocks (most query tiles under a causal mask) of all heads and sequences first
+    const int per = nkv * n_seqs;
+    const int g = (blockIdx.x % per) % nkv, b = (blockIdx.x % per) / nkv;
     const int s0 = cu[b], s1 = cu[b + 1];
-    const int kblk = blockIdx.x * BK_;                      // first key of the workgroup, relative to s0
+    const int kblk = (int)(blockIdx.x / per) * BK_;         // first key of the workgroup, relative to s0
     if (kblk >= s1 - s0) return;
     const int grp = nq / nkv;
-    const long ld = (long)(nq + 2 * nkv) * HD;
+    const long ld = (long)(nq + 2 * nkv) * HD, ldo = (long)nq * HD;
     const int key = s0 + kblk + wave * 32 + lrow;           // this lane's key (token index)
     const bool kok = key < s1;
     const float c = scale * 1.4426950408889634f;
+    const __amdgpu_buffer_rsrc_t rq = make_rsrc(qkv, (long)n * ld * 2), ro = make_rsrc(d_o, (long)n * ldo * 2);
 
     bf16x8 kf[D::KST], vf[D::KST];
     {
@@ -412,35 +398,18 @@ __global__ __launch_bounds__(256) void attn_bwd_dkv_mfma_kernel(const bf16_t *__
     const int nqt = (s1 - s0 + BQ - 1) / BQ - qt_first;
     const int niter = nqt * grp;
 
-    Stager<64, false> sq[D::NKS], sdo[D::NKS];
-    Stager<D::DB * 32, true> sqt, sdot;
-    float r_lse = 0.f, r_dlt = 0.f;
-    auto load_tile = [&](int it) {
+    auto issue = [&](int it, bf16_t *qt_, bf16_t *ot_, float *f) {
         const int h = g * grp + it / nqt;
         const int qs = s0 + (qt_first + it % nqt) * BQ;
-        const bf16_t *Qb = qkv + (long)h * HD;
-        const bf16_t *Ob = d_o + (long)h * HD;
+        constexpr int PER = 4 * D::NKS;
 #pragma unroll
-        for (int i = 0; i < D::NKS; ++i) {
-            sq[i].load(Qb, ld, qs, s1, i * 64, HD, tid);
-            sdo[i].load(Ob, (long)nq * HD, qs, s1, i * 64, HD, tid);
+        for (int i = 0; i < PER; ++i) {
+            const int idx = wave * PER + i;
+            if (idx < 8 * D::NKS) attn_dma<HD>(rq, qt_, qs, ld, h * HD, idx, lane);
+            else attn_dma<HD>(ro, ot_, qs, ldo, h * HD, idx - 8 * D::NKS, lane);
         }
-        sqt.load(Qb, ld, 0, HD, qs, s1, tid);
-        sdot.load(Ob, (long)nq * HD, 0, HD, qs, s1, tid);
-        if (tid < 64) r_lse = qs + tid < s1 ? lse[(long)h * n + qs + tid] * 1.4426950408889634f : 0.f;
-        else if (tid < 128) r_dlt = qs + tid - 64 < s1 ? delta[(long)h * n + qs + tid - 64] : 0.f;
-    };
-    auto store_tile = [&](int buf) {
-        bf16_t *base = sm + buf * BUF;
-#pragma unroll
-        for (int i = 0; i < D::NKS; ++i) {
-            sq[i].store(base + i * 64 * 64, tid);
-            sdo[i].store(base + RM + i * 64 * 64, tid);
-        }
-        sqt.store(base + 2 * RM, tid);
-        sdot.store(base + 2 * RM + TR, tid);
-        if (tid < 64) sf[buf * 128 + tid] = r_lse;
-        else if (tid < 128) sf[buf * 128 + tid] = r_dlt;
+        if (tid < 64) f[tid] = qs + tid < s1 ? lse[(long)h * n + qs + tid] * 1.4426950408889634f : 0.f;
+        else if (tid < 128) f[tid] = qs + tid - 64 < s1 ? delta[(long)h * n + qs + tid - 64] : 0.f;
     };
 
     f32x16 dk[D::DB], dv[D::DB];
@@ -449,17 +418,8 @@ __global__ __launch_bounds__(256) void attn_bwd_dkv_mfma_kernel(const bf16_t *__
 #pragma unroll
         for (int r = 0; r < 16; ++r) { dk[i][r] = 0.f; dv[i][r] = 0.f; }
 
-    if (niter > 0) {
-        load_tile(0);
-        store_tile(0);
-    }
-    __syncthreads();
-
-    for (int it = 0; it < niter; ++it) {
-        const int cur = it & 1;
-        if (it + 1 < niter) load_tile(it + 1);
-        const bf16_t *qt_ = sm + cur * BUF, *dot_ = qt_ + RM, *qtt = qt_ + 2 * RM, *dott = qtt + TR;
-        const float *ls = sf + cur * 128, *dl = ls + 64;
+    auto compute = [&](int it, const bf16_t *qt_, const bf16_t *ot_, const float *f) {
+        const float *ls = f, *dl = f + 64;
         const int qs = s0 + (qt_first + it % nqt) * BQ;
 #pragma unroll
         for (int qb = 0; qb < 2; ++qb) {
@@ -468,9 +428,9 @@ __global__ __launch_bounds__(256) void attn_bwd_dkv_mfma_kernel(const bf16_t *__
             for (int r = 0; r < 16; ++r) { st[r] = 0.f; dp[r] = 0.f; }
 #pragma unroll
             for (int ks = 0; ks < D::KST; ++ks) {
-                const int off = (ks / 4) * 64 * 64 + lds_off(qb * 32 + lrow, (ks % 4) * 2 + half);
+                const int off = (ks / 4) * 4096 + lds_off(qb * 32 + lrow, (ks % 4) * 2 + half);
                 st = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*(const bf16x8 *)(qt_ + off), kf[ks], st, 0, 0, 0);
-                dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*(const bf16x8 *)(dot_ + off), vf[ks], dp, 0, 0, 0);
+                dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*(const bf16x8 *)(ot_ + off), vf[ks], dp, 0, 0, 0);
             }
             // accumulator rows are queries qb*32 + 8*(r/4) + 4*half + r%4, the column is this lane's key
             float p[16], ds[16];
@@ -493,12 +453,21 @@ __global__ __launch_bounds__(256) void attn_bwd_dkv_mfma_kernel(const bf16_t *__
                 const bf16x8 pf = pack8(&p[8 * t]), dsf = pack8(&ds[8 * t]);
 #pragma unroll
                 for (int db = 0; db < D::DB; ++db) {
-                    dv[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(pf, load_tr_frag(dott, db * 32 + lrow, qb * 4 + 2 * t, half), dv[db], 0, 0, 0);
-                    dk[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(dsf, load_tr_frag(qtt, db * 32 + lrow, qb * 4 + 2 * t, half), dk[db], 0, 0, 0);
+                    dv[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(pf, attn_tr_frag(ot_, qb * 32 + 16 * t, db * 32, lane), dv[db], 0, 0, 0);
+                    dk[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(dsf, attn_tr_frag(qt_, qb * 32 + 16 * t, db * 32, lane), dk[db], 0, 0, 0);
                 }
             }
         }
-        if (it + 1 < niter) store_tile(cur ^ 1);
+    };
+
+    issue(0, Q0, O0, F0);
+    __syncthreads();
+    for (int it = 0; it < niter; it += 2) {
+        if (it + 1 < niter) issue(it + 1, Q1, O1, F1);
+        compute(it, Q0, O0, F0);
+        __syncthreads();
+        if (it + 2 < niter) issue(it + 2, Q0, O0, F0);
+        if (it + 1 < niter) compute(it + 1, Q1, O1, F1);
         __syncthreads();
     }
 
@@ -536,29 +505,23 @@ ms_status launch_fwd(int causal, int nq, int nkv, int n, int n_seqs, int max_seq
 template <int HD>
 ms_status launch_bwd(int causal, int nq, int nkv, int n, int n_seqs, int max_seqlen, const int *cu, const void *qkv,
                      const void *o, const float *lse, const void *d_o, void *dqkv, void *scratch, hipStream_t s) {
-    using D = AttnDims<HD>;
     float *delta = (float *)scratch;
     attn_delta_kernel<<<ms_cdiv((long)n * nq, 256), 256, 0, s>>>((const bf16_t *)o, (const bf16_t *)d_o, delta, n, nq, HD);
     MS_LAUNCH_CHECK();
     const float scale = 1.f / sqrtf((float)HD);
-    const size_t smem_dq = (size_t)2 * (2 * D::NKS * 64 * 64 + D::DB * 32 * 64) * sizeof(bf16_t);
-    const size_t smem_dkv = (size_t)2 * (2 * D::NKS * 64 * 64 + 2 * D::DB * 32 * 64) * sizeof(bf16_t) + 2 * 128 * sizeof(float);
-    dim3 grid_dq(ms_cdiv(max_seqlen, 128), nq, n_seqs), grid_dkv(ms_cdiv(max_seqlen, 128), nkv, n_seqs);
+    const int ntile_max = ms_cdiv(max_seqlen, 128);
+    const long blocks = (long)ntile_max * nq * n_seqs;
+    if (blocks > 0x7fffffffL || (long)n * (nq + 2 * nkv) * HD * 2 >= (1L << 32) - (1L << 20))
+        return ms_fail(MS_ERR_UNSUPPORTED, "attention: batch too large for 32-bit tile offsets");
+    const unsigned grid_dkv = (unsigned)((long)ntile_max * nkv * n_seqs);
 #define GO(C)                                                                                                          \
     do {                                                                                                               \
-        static bool attr_set = false;                                                                                  \
-        if (!attr_set) {                                                                                               \
-            MS_CHECK_HIP(hipFuncSetAttribute((const void *)attn_bwd_dq_mfma_kernel<HD, C>,                             \
-                                             hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem_dq));               \
-            MS_CHECK_HIP(hipFuncSetAttribute((const void *)attn_bwd_dkv_mfma_kernel<HD, C>,                            \
-                                             hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem_dkv));              \
-            attr_set = true;                                                                                           \
-        }                                                                                                              \
-        attn_bwd_dq_mfma_kernel<HD, C><<<grid_dq, 256, smem_dq, s>>>((const bf16_t *)qkv, (const bf16_t *)d_o, lse,    \
-                                                                      delta, (bf16_t *)dqkv, cu, n, nq, nkv, scale);   \
+        attn_bwd_dq_mfma_kernel<HD, C><<<(unsigned)blocks, 256, 0, s>>>((const bf16_t *)qkv, (const bf16_t *)d_o, lse, \
+                                                                        delta, (bf16_t *)dqkv, cu, n, nq, nkv, n_seqs, \
+                                                                        ntile_max, scale);                             \
         MS_LAUNCH_CHECK();                                                                                             \
-        attn_bwd_dkv_mfma_kernel<HD, C><<<grid_dkv, 256, smem_dkv, s>>>((const bf16_t *)qkv, (const bf16_t *)d_o, lse, \
-                                                                         delta, (bf16_t *)dqkv, cu, n, nq, nkv, scale);\
+        attn_bwd_dkv_mfma_kernel<HD, C><<<grid_dkv, 256, 0, s>>>((const bf16_t *)qkv, (const bf16_t *)d_o, lse, delta, \
+                                                                 (bf16_t *)dqkv, cu, n, nq, nkv, n_seqs, scale);       \
     } while (0)
     if (causal) GO(true); else GO(false);
 #undef GO
