@@ -15,6 +15,14 @@ this between two oracle runs that differ by 1e-6 relative perturbations).  With 
 the 2e-2 bound is a 5-sigma event, so on tensors of 10^5 .. 10^7 elements a handful of elements
 may exceed it although nothing is wrong.  The chain criterion therefore requires
   rms(err) <= tol / 3,  99.9 % of the elements <= tol,  every element <= 3 tol.
+
+assert_parity_vs_noise: for deep, wide stacks (the full-size workloads: 4-8 layers at d = 1024..4096)
+that rounding noise itself exceeds the chain numbers: two runs of the ORACLE under the bf16 contract,
+differing only by 1e-6 relative perturbations before each rounding, differ by ~1e-2 rms / 3.5e-2 at
+p99.9 on the c2 teacher (random N(0, 0.02) weights make the net sensitive).  There the HIP result is
+held to that measured floor: its error against the oracle may not exceed 1.5 x the error of the
+perturbed oracle run against the same oracle (rms and p99.9; 2 x for the maximum), with absolute caps
+so the check cannot become vacuous.
 """
 import numpy as np
 import torch
@@ -50,3 +58,26 @@ def assert_parity_chain(gpu, ref, tol, name=""):
     assert rms <= tol / 3 and q <= tol and mx <= 3 * tol, \
         f"{name}: rms {rms:.3e} (<= {tol / 3:.1e}), p99.9 {q:.3e} (<= {tol:.1e}), max {mx:.3e} (<= {3 * tol:.1e})"
     return mx
+
+
+def perturbed_rounding(seed, rel=1e-6):
+    """(rnd, rnd_res) like (round_bf16, round_f32) but with a relative perturbation of size `rel` applied
+    first: a stand-in for a second correct bf16 implementation (different accumulation order)."""
+    from oracle import round_bf16, round_f32
+    rng = np.random.default_rng(seed)
+
+    def jitter(x):
+        x = np.asarray(x, dtype=np.float64)
+        return x * (1.0 + rel * rng.standard_normal(x.shape))
+    return (lambda x: round_bf16(jitter(x))), (lambda x: round_f32(jitter(x)))
+
+
+def assert_parity_vs_noise(gpu, ref, ref_perturbed, name="", factor=1.5, cap_rms=2e-2, cap_max=0.15):
+    e, f = rel_err(gpu, ref), rel_err(ref_perturbed, ref)
+    assert np.all(np.isfinite(e)), f"{name}: non-finite values"
+    stats = lambda v: (float(np.sqrt(np.mean(v * v))), float(np.quantile(v, 0.999)), float(v.max()))
+    (er, eq, em), (fr, fq, fm) = stats(e), stats(f)
+    msg = f"{name}: gpu-vs-oracle rms {er:.3e} p99.9 {eq:.3e} max {em:.3e}; noise floor rms {fr:.3e} p99.9 {fq:.3e} max {fm:.3e}"
+    assert er <= factor * fr and eq <= factor * fq and em <= 2 * factor * fm, msg
+    assert er <= cap_rms and em <= cap_max, msg
+    return msg
