@@ -22,6 +22,10 @@
 
 namespace {
 
+// gcc-style vectors: the return types of the buffer load builtins
+typedef unsigned int u32x4 __attribute__((vector_size(16)));
+typedef unsigned int u32x2 __attribute__((vector_size(8)));
+
 struct GemmParams {
     const void *A, *B;
     void *C;
@@ -31,7 +35,7 @@ struct GemmParams {
     int tiles_m, tiles_n;
     int k_tiles_per_split;  // in units of 64
     float alpha;
-    int c_fp32, accumulate, atomic, res_fp32;
+    int c_fp32, accumulate, atomic, res_fp32, vec_epilogue;
 };
 
 template <int BM, int BN, bool TA, bool TB>
@@ -282,12 +286,84 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_bf16_fast_kernel(GemmParams
         __syncthreads();
     }
 
-    // epilogue through buffer descriptors: offsets past the range are dropped (stores) or read 0
+    // ---- epilogue.  C and the residual are addressed through buffer descriptors: rows past M are
+    // dropped (stores) or read as zero by the range check, columns past N by one select.
     const int esz = p.c_fp32 ? 4 : 2;
     const __amdgpu_buffer_rsrc_t rc = make_rsrc(p.C, (long)p.M * p.ldc * esz);
     const int rsz = p.res_fp32 ? 4 : 2;
     const __amdgpu_buffer_rsrc_t rr = make_rsrc(p.residual ? p.residual : p.C, p.residual ? (long)p.M * p.ldr * rsz : 0);
     const bf16_t *bias = (const bf16_t *)p.bias;
+    if (p.vec_epilogue) {
+        // Each wave passes its accumulators through LDS, 32 rows at a time, to turn the MFMA layout
+        // (a lane owns one column) into rows: a lane then handles 4 consecutive columns of a row, so
+        // residual reads and C writes are 8..16 bytes per lane and 128..256 contiguous bytes per row.
+        static_assert(WTN == 64, "staging assumes 64-column wave tiles");
+        constexpr int WPA = BM / 64;                       // waves sharing one of the (now idle) A buffers
+        float *stg = (float *)((wave / WPA) ? As1 : As0) + (wave % WPA) * 2048;
+        const int prow = lane >> 4, pcol = (lane & 15) * 4;
+        const int colg = n0 + wn * WTN + pcol;
+        const bool cok = colg < p.N;
+        float bv[4] = {0.f, 0.f, 0.f, 0.f};
+        if (bias && cok) {
+            const uint2 b2 = *(const uint2 *)(bias + colg);
+            bv[0] = (float)__builtin_bit_cast(bf16_t, (unsigned short)(b2.x & 0xffff));
+            bv[1] = (float)__builtin_bit_cast(bf16_t, (unsigned short)(b2.x >> 16));
+            bv[2] = (float)__builtin_bit_cast(bf16_t, (unsigned short)(b2.y & 0xffff));
+            bv[3] = (float)__builtin_bit_cast(bf16_t, (unsigned short)(b2.y >> 16));
+        }
+#pragma unroll
+        for (int i = 0; i < MI; ++i) {
+            // accumulators -> LDS [32 rows][64 columns] fp32; column bit 5 is flipped for rows 4..7 (mod 8)
+            // so that the two half-waves (rows 4 apart) use different banks
+#pragma unroll
+            for (int j = 0; j < NI; ++j)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    const int row = 8 * (r >> 2) + 4 * fhalf + (r & 3);
+                    stg[row * 64 + ((j * 32 + frow) ^ (fhalf << 5))] = acc[i][j][r] * p.alpha;
+                }
+#pragma unroll
+            for (int ps = 0; ps < 8; ++ps) {
+                const int row = ps * 4 + prow;
+                const float4 t = *(const float4 *)(stg + row * 64 + (pcol ^ (((row >> 2) & 1) << 5)));
+                float v[4] = {t.x + bv[0], t.y + bv[1], t.z + bv[2], t.w + bv[3]};
+                const long rowg = m0 + wm * WTM + i * 32 + row;
+                if (p.residual) {
+                    const unsigned ro = cok ? (unsigned)((rowg * p.ldr + colg) * rsz) : kOob;
+                    if (p.res_fp32) {
+                        const u32x4 q = __builtin_amdgcn_raw_buffer_load_b128(rr, ro, 0, 0);
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) v[e] += __uint_as_float(q[e]);
+                    } else {
+                        const u32x2 q = __builtin_amdgcn_raw_buffer_load_b64(rr, ro, 0, 0);
+                        v[0] += (float)__builtin_bit_cast(bf16_t, (unsigned short)(q[0] & 0xffff));
+                        v[1] += (float)__builtin_bit_cast(bf16_t, (unsigned short)(q[0] >> 16));
+                        v[2] += (float)__builtin_bit_cast(bf16_t, (unsigned short)(q[1] & 0xffff));
+                        v[3] += (float)__builtin_bit_cast(bf16_t, (unsigned short)(q[1] >> 16));
+                    }
+                }
+                const unsigned co = cok ? (unsigned)((rowg * p.ldc + colg) * esz) : kOob;
+                if (p.c_fp32) {
+                    if (p.accumulate) {
+                        const u32x4 q = __builtin_amdgcn_raw_buffer_load_b128(rc, co, 0, 0);
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) v[e] += __uint_as_float(q[e]);
+                    }
+                    u32x4 w;
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) w[e] = __builtin_bit_cast(unsigned, v[e]);
+                    __builtin_amdgcn_raw_buffer_store_b128(w, rc, co, 0, 0);
+                } else {
+                    u32x2 w;
+                    w[0] = (unsigned)__builtin_bit_cast(unsigned short, (bf16_t)v[0]) | ((unsigned)__builtin_bit_cast(unsigned short, (bf16_t)v[1]) << 16);
+                    w[1] = (unsigned)__builtin_bit_cast(unsigned short, (bf16_t)v[2]) | ((unsigned)__builtin_bit_cast(unsigned short, (bf16_t)v[3]) << 16);
+                    __builtin_amdgcn_raw_buffer_store_b64(w, rc, co, 0, 0);
+                }
+            }
+        }
+        return;
+    }
+    // scalar epilogue: split-K atomics and shapes whose rows are not 4-element aligned
 #pragma unroll
     for (int j = 0; j < NI; ++j) {
         const int col = n0 + wn * WTN + j * 32 + frow;
@@ -472,6 +548,9 @@ extern "C" ms_status ms_k_gemm(int32_t dtype, int32_t trans_a, int32_t trans_b, 
     p.k_tiles_per_split = ms_cdiv(kt_total, splits);
     splits = ms_cdiv(kt_total, p.k_tiles_per_split);
     p.atomic = splits > 1;
+    auto al16 = [](const void *q) { return ((uintptr_t)q & 15) == 0; };
+    p.vec_epilogue = !p.atomic && N % 4 == 0 && ldc % 4 == 0 && al16(C) && (!residual || (ldr % 4 == 0 && al16(residual))) &&
+                     (!bias || ((uintptr_t)bias & 7) == 0);
     if (big) return launch_bf16_fast<256, 256, 2, 4>(p, trans_a, trans_b, splits, s);
     if (fast) return launch_bf16_fast<128, 128, 2, 2>(p, trans_a, trans_b, splits, s);
     return launch_bf16<128, 128>(p, trans_a, trans_b, splits, s);
