@@ -28,31 +28,6 @@ __device__ __forceinline__ bf16x8 pack8(const float *v) {
     return r;
 }
 
-// One direct-to-LDS instruction of a row-major tile [64 rows][HD] kept as NKS sub-tiles [64][64]:
-// instruction idx fills 8-row group idx % 8 of sub-tile idx / 8 from rows row0.. of a matrix with
-// leading dimension ld (elements), starting at column col0.  Columns past HD arrive as zeros.
-template <int HD>
-__device__ __forceinline__ void attn_dma(__amdgpu_buffer_rsrc_t rs, bf16_t *tile, int row0, long ld, int col0, int idx,
-                                         int lane) {
-    const int sub = idx >> 3, g = idx & 7;
-    const int r = g * 8 + (lane >> 3);
-    const int c = (lane & 7) ^ (lane >> 3) ^ (g & 3);
-    const int d = sub * 64 + c * 8;
-    const unsigned voff = d < HD ? (unsigned)(((long)(row0 + r) * ld + col0 + d) * 2) : kOob;
-    __builtin_amdgcn_raw_ptr_buffer_load_lds(rs, (lds_void *)(tile + sub * 4096 + g * 512), 16, voff, 0, 0, 0);
-}
-
-// A-operand fragment (rows = 32 consecutive columns m of the tile starting at m0, k-slots = tile
-// rows k0 + 4h + {0..3} and k0 + 8 + 4h + {0..3}) of a row-major tile [64][HD], read transposed.
-__device__ __forceinline__ bf16x8 attn_tr_frag(const bf16_t *tile, int k0, int m0, int lane) {
-    const int h = lane >> 5, dg = (lane >> 4) & 1, r = lane & 15;
-    const int row = k0 + 4 * h + (r >> 2);
-    const int m = m0 + 16 * dg + 4 * (r & 3);
-    const bf16_t *base = tile + (m >> 6) * 4096 + (m & 7);
-    const int chunk = (m & 63) >> 3;
-    return tr_frag(base + lds_off(row, chunk), base + lds_off(row + 8, chunk));
-}
-
 template <int HD, bool CAUSAL>
 __global__ __launch_bounds__(256) void attn_fwd_mfma_kernel(const bf16_t *__restrict__ qkv, bf16_t *__restrict__ o,
                                                              float *__restrict__ lse, const int *__restrict__ cu, int n,
@@ -97,8 +72,8 @@ __global__ __launch_bounds__(256) void attn_fwd_mfma_kernel(const bf16_t *__rest
 #pragma unroll
         for (int i = 0; i < PER; ++i) {
             const int idx = wave * PER + i;
-            if (idx < 8 * D::NKS) attn_dma<HD>(rs, kt, s0 + j * BKV, ld, kcol, idx, lane);
-            else attn_dma<HD>(rs, vt, s0 + j * BKV, ld, vcol, idx - 8 * D::NKS, lane);
+            if (idx < 8 * D::NKS) rowtile_dma<HD>(rs, kt, s0 + j * BKV, ld, kcol, idx, lane);
+            else rowtile_dma<HD>(rs, vt, s0 + j * BKV, ld, vcol, idx - 8 * D::NKS, lane);
         }
     };
 
@@ -167,7 +142,7 @@ __global__ __launch_bounds__(256) void attn_fwd_mfma_kernel(const bf16_t *__rest
                 const bf16x8 pf = pack8(&p[kb][8 * t]);
 #pragma unroll
                 for (int db = 0; db < D::DB; ++db)
-                    oacc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(attn_tr_frag(vt, kb * 32 + 16 * t, db * 32, lane), pf,
+                    oacc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(rowtile_tr_frag(vt, kb * 32 + 16 * t, db * 32, lane), pf,
                                                                          oacc[db], 0, 0, 0);
             }
     };
@@ -276,8 +251,8 @@ __global__ __launch_bounds__(256) void attn_bwd_dq_mfma_kernel(const bf16_t *__r
 #pragma unroll
         for (int i = 0; i < PER; ++i) {
             const int idx = wave * PER + i;
-            if (idx < 8 * D::NKS) attn_dma<HD>(rs, kt, s0 + j * BKV, ld, kcol, idx, lane);
-            else attn_dma<HD>(rs, vt, s0 + j * BKV, ld, vcol, idx - 8 * D::NKS, lane);
+            if (idx < 8 * D::NKS) rowtile_dma<HD>(rs, kt, s0 + j * BKV, ld, kcol, idx, lane);
+            else rowtile_dma<HD>(rs, vt, s0 + j * BKV, ld, vcol, idx - 8 * D::NKS, lane);
         }
     };
 
@@ -313,7 +288,7 @@ __global__ __launch_bounds__(256) void attn_bwd_dq_mfma_kernel(const bf16_t *__r
                 const bf16x8 dsf = pack8(&ds[8 * t]);
 #pragma unroll
                 for (int db = 0; db < D::DB; ++db)
-                    dq[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(attn_tr_frag(kt, kb * 32 + 16 * t, db * 32, lane), dsf,
+                    dq[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(rowtile_tr_frag(kt, kb * 32 + 16 * t, db * 32, lane), dsf,
                                                                        dq[db], 0, 0, 0);
             }
         }
@@ -405,8 +380,8 @@ __global__ __launch_bounds__(256) void attn_bwd_dkv_mfma_kernel(const bf16_t *__
 #pragma unroll
         for (int i = 0; i < PER; ++i) {
             const int idx = wave * PER + i;
-            if (idx < 8 * D::NKS) attn_dma<HD>(rq, qt_, qs, ld, h * HD, idx, lane);
-            else attn_dma<HD>(ro, ot_, qs, ldo, h * HD, idx - 8 * D::NKS, lane);
+            if (idx < 8 * D::NKS) rowtile_dma<HD>(rq, qt_, qs, ld, h * HD, idx, lane);
+            else rowtile_dma<HD>(ro, ot_, qs, ldo, h * HD, idx - 8 * D::NKS, lane);
         }
         if (tid < 64) f[tid] = qs + tid < s1 ? lse[(long)h * n + qs + tid] * 1.4426950408889634f : 0.f;
         else if (tid < 128) f[tid] = qs + tid - 64 < s1 ? delta[(long)h * n + qs + tid - 64] : 0.f;
@@ -453,8 +428,8 @@ __global__ __launch_bounds__(256) void attn_bwd_dkv_mfma_kernel(const bf16_t *__
                 const bf16x8 pf = pack8(&p[8 * t]), dsf = pack8(&ds[8 * t]);
 #pragma unroll
                 for (int db = 0; db < D::DB; ++db) {
-                    dv[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(pf, attn_tr_frag(ot_, qb * 32 + 16 * t, db * 32, lane), dv[db], 0, 0, 0);
-                    dk[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(dsf, attn_tr_frag(qt_, qb * 32 + 16 * t, db * 32, lane), dk[db], 0, 0, 0);
+                    dv[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(pf, rowtile_tr_frag(ot_, qb * 32 + 16 * t, db * 32, lane), dv[db], 0, 0, 0);
+                    dk[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(dsf, rowtile_tr_frag(qt_, qb * 32 + 16 * t, db * 32, lane), dk[db], 0, 0, 0);
                 }
             }
         }

@@ -219,11 +219,11 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_bf16_fast_kernel(GemmParams
     if (nk <= 0) return;
 
     const bf16_t *A = (const bf16_t *)p.A, *B = (const bf16_t *)p.B;
-    Stager<BM, true, NT> sa;          // used only when TA
-    Stager<BN, true, NT> sb;          // used only when TB
     DmaStager<BM, WM * WN> da;        // used only when !TA
     DmaStager<BN, WM * WN> db;
-    const __amdgpu_buffer_rsrc_t ra = make_rsrc(A, (long)p.M * p.lda * 2), rb = make_rsrc(B, (long)p.N * p.ldb * 2);
+    // descriptor ranges: rows x leading dimension of the matrix as stored ([M or N][K], or [K][M or N])
+    const __amdgpu_buffer_rsrc_t ra = make_rsrc(A, TA ? ((long)(p.K - 1) * p.lda + p.M) * 2 : ((long)(p.M - 1) * p.lda + p.K) * 2);
+    const __amdgpu_buffer_rsrc_t rb = make_rsrc(B, TB ? ((long)(p.K - 1) * p.ldb + p.N) * 2 : ((long)(p.N - 1) * p.ldb + p.K) * 2);
     if constexpr (!TA) da.init(p.lda, m0, lane);
     if constexpr (!TB) db.init(p.ldb, n0, lane);
 
@@ -235,28 +235,45 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_bf16_fast_kernel(GemmParams
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
-    // start moving K tile kt towards LDS; a tile past the end of this workgroup's K range arrives as zeros
+    // Start moving K tile kt towards LDS; a tile past the end of this workgroup's K range arrives as zeros.
+    // An operand stored K-major ([K][M]) is loaded as a "row tile" (64 k-rows x BM columns) and read back
+    // through the transposing LDS load, so every layout goes global -> LDS without staging registers.
     auto fetch = [&](int kt, bf16_t *as, bf16_t *bs) {
         const bool valid = kt < nk;
         const int k0 = (kt_begin + kt) * BK;
-        const int k_end = valid ? p.K : 0;
-        if constexpr (TA) sa.load(A, p.lda, m0, p.M, k0, k_end, tid); else da.issue(ra, as, k0, wave, valid);
-        if constexpr (TB) sb.load(B, p.ldb, n0, p.N, k0, k_end, tid); else db.issue(rb, bs, k0, wave, valid);
-    };
-    auto commit = [&](bf16_t *as, bf16_t *bs) {          // register-staged operands: write them to LDS
-        if constexpr (TA) sa.store(as, tid);
-        if constexpr (TB) sb.store(bs, tid);
+        constexpr int PA = BM / 8 / (WM * WN), PB = BN / 8 / (WM * WN);
+        if constexpr (TA) {
+#pragma unroll
+            for (int i = 0; i < PA; ++i) rowtile_dma<BM>(ra, as, k0, p.lda, m0, wave * PA + i, lane, valid);
+        } else {
+            da.issue(ra, as, k0, wave, valid);
+        }
+        if constexpr (TB) {
+#pragma unroll
+            for (int i = 0; i < PB; ++i) rowtile_dma<BN>(rb, bs, k0, p.ldb, n0, wave * PB + i, lane, valid);
+        } else {
+            db.issue(rb, bs, k0, wave, valid);
+        }
     };
     const int frow = lane & 31, fhalf = lane >> 5;
     auto compute = [&](const bf16_t *as, const bf16_t *bs) {
         bf16x8 af[2][MI], bfr[2][NI];
+        // when either operand is K-major both use its k-slot order (two 8-byte reads for the other one)
         auto load_frags = [&](int kk, int slot) {
 #pragma unroll
-            for (int i = 0; i < MI; ++i)
-                af[slot][i] = *(const bf16x8 *)(as + lds_off(wm * WTM + i * 32 + frow, kk * 2 + fhalf));
+            for (int i = 0; i < MI; ++i) {
+                const int row = wm * WTM + i * 32;
+                if constexpr (TA) af[slot][i] = rowtile_tr_frag(as, kk * 16, row, lane);
+                else if constexpr (TB) af[slot][i] = ktile_frag_paired(as, row + frow, kk, fhalf);
+                else af[slot][i] = *(const bf16x8 *)(as + lds_off(row + frow, kk * 2 + fhalf));
+            }
 #pragma unroll
-            for (int j = 0; j < NI; ++j)
-                bfr[slot][j] = *(const bf16x8 *)(bs + lds_off(wn * WTN + j * 32 + frow, kk * 2 + fhalf));
+            for (int j = 0; j < NI; ++j) {
+                const int row = wn * WTN + j * 32;
+                if constexpr (TB) bfr[slot][j] = rowtile_tr_frag(bs, kk * 16, row, lane);
+                else if constexpr (TA) bfr[slot][j] = ktile_frag_paired(bs, row + frow, kk, fhalf);
+                else bfr[slot][j] = *(const bf16x8 *)(bs + lds_off(row + frow, kk * 2 + fhalf));
+            }
         };
         load_frags(0, 0);
 #pragma unroll
@@ -271,18 +288,15 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_bf16_fast_kernel(GemmParams
     };
 
     fetch(0, As0, Bs0);
-    commit(As0, Bs0);
     __syncthreads();
     // two K tiles per trip so that each half names its LDS buffers statically; an odd tile count is
     // rounded up with a tile of zeros (a single loop exit keeps the accumulators in place)
     for (int kt = 0; kt < nk; kt += 2) {
         fetch(kt + 1, As1, Bs1);
         compute(As0, Bs0);
-        commit(As1, Bs1);
         __syncthreads();
         if (kt + 2 < nk) fetch(kt + 2, As0, Bs0);
         compute(As1, Bs1);
-        if (kt + 2 < nk) commit(As0, Bs0);
         __syncthreads();
     }
 

@@ -38,6 +38,42 @@ __device__ __forceinline__ bf16x8 tr_frag(const bf16_t *p0, const bf16_t *p1) {
     return __builtin_shufflevector(a, b, 0, 1, 2, 3, 4, 5, 6, 7);
 }
 
+// ---- "row tiles": 64 rows x W columns of a row-major matrix, kept as W/64 sub-tiles [64][64] --------
+// One direct-to-LDS instruction: instruction idx fills 8-row group idx % 8 of sub-tile idx / 8 from rows
+// row0.. of a matrix with leading dimension ld (elements), starting at column col0.  Columns past W
+// arrive as zeros; rows past the end of the matrix are zeroed by the descriptor's range check.
+template <int W>
+__device__ __forceinline__ void rowtile_dma(__amdgpu_buffer_rsrc_t rs, bf16_t *tile, int row0, long ld, int col0, int idx,
+                                            int lane, bool valid = true) {
+    const int sub = idx >> 3, g = idx & 7;
+    const int r = g * 8 + (lane >> 3);
+    const int c = (lane & 7) ^ (lane >> 3) ^ (g & 3);
+    const int d = sub * 64 + c * 8;
+    const unsigned voff = (valid && d < W) ? (unsigned)(((long)(row0 + r) * ld + col0 + d) * 2) : kOob;
+    __builtin_amdgcn_raw_ptr_buffer_load_lds(rs, (lds_void *)(tile + sub * 4096 + g * 512), 16, voff, 0, 0, 0);
+}
+
+// MFMA operand fragment whose 32 "rows" are tile columns m0 .. m0+31 and whose k-slots are tile rows:
+// half h of the wave gets rows k0 + 4h + {0..3} (slots 0..3) and k0 + 8 + 4h + {0..3} (slots 4..7).
+__device__ __forceinline__ bf16x8 rowtile_tr_frag(const bf16_t *tile, int k0, int m0, int lane) {
+    const int h = lane >> 5, dg = (lane >> 4) & 1, r = lane & 15;
+    const int row = k0 + 4 * h + (r >> 2);
+    const int m = m0 + 16 * dg + 4 * (r & 3);
+    const bf16_t *base = tile + (m >> 6) * 4096 + (m & 7);
+    const int chunk = (m & 63) >> 3;
+    return tr_frag(base + lds_off(row, chunk), base + lds_off(row + 8, chunk));
+}
+
+// Fragment of a K-contiguous tile [rows][64] with the SAME k-slot order as rowtile_tr_frag (for MFMAs
+// that pair one operand of each kind): two 8-byte reads instead of one 16-byte read.
+__device__ __forceinline__ bf16x8 ktile_frag_paired(const bf16_t *tile, int row, int kk, int half) {
+    const uint2 lo = *(const uint2 *)(tile + lds_off(row, kk * 2) + 4 * half);
+    const uint2 hi = *(const uint2 *)(tile + lds_off(row, kk * 2 + 1) + 4 * half);
+    union { uint4 u; bf16x8 v; } f;
+    f.u = make_uint4(lo.x, lo.y, hi.x, hi.y);
+    return f.v;
+}
+
 __device__ __forceinline__ uint32_t pack_lo(uint32_t a, uint32_t b) { return (a & 0xffffu) | (b << 16); }
 __device__ __forceinline__ uint32_t pack_hi(uint32_t a, uint32_t b) { return (a >> 16) | (b & 0xffff0000u); }
 

@@ -30,7 +30,7 @@ def tol_of(dtype):
 
 
 @pytest.mark.parametrize("ta,tb", [(0, 0), (0, 1), (1, 0), (1, 1)])
-@pytest.mark.parametrize("M,N,K", [(300, 200, 136), (128, 128, 64), (1, 8, 8), (513, 344, 1000), (264, 1032, 72)])
+@pytest.mark.parametrize("M,N,K", [(300, 200, 136), (128, 128, 64), (1, 8, 8), (513, 344, 1000), (264, 1032, 72), (392, 520, 192)])
 def test_gemm_bf16_all_layouts(ta, tb, M, N, K):
     if (ta and M % 8) or (tb and N % 8) or ((not ta or not tb) and K % 8):
         pytest.skip("shape not 16-byte aligned for this layout")
