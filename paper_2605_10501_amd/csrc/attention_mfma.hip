@@ -327,11 +327,15 @@ __global__ __launch_bounds__(256) void attn_bwd_dq_mfma_kernel(const bf16_t *__r
 // dK += dS^T Q; their B operands (dO and Q with queries as the contraction index) come from the
 // row-major tiles through the transposing LDS load.  The sums over the query group stay in
 // registers: no atomics.
-template <int HD, bool CAUSAL>
+// SPLIT: one workgroup per query head of the group instead of one per K/V head (4x the workgroups and a 4x
+// shorter longest one under grouped-query attention); partial dK/dV are then summed with fp32 atomics
+// into dkv_acc [n][2][nkv * HD], which attn_dkv_store_kernel rounds into dqkv afterwards.
+template <int HD, bool CAUSAL, bool SPLIT>
 __global__ __launch_bounds__(256) void attn_bwd_dkv_mfma_kernel(const bf16_t *__restrict__ qkv, const bf16_t *__restrict__ d_o,
                                                                  const float *__restrict__ lse, const float *__restrict__ delta,
-                                                                 bf16_t *__restrict__ dqkv, const int *__restrict__ cu, int n,
-                                                                 int nq, int nkv, int n_seqs, float scale) {
+                                                                 bf16_t *__restrict__ dqkv, float *__restrict__ dkv_acc,
+                                                                 const int *__restrict__ cu, int n, int nq, int nkv,
+                                                                 int n_seqs, float scale) {
     using D = AttnDims<HD>;
     constexpr int BK_ = 128, BQ = 64, TS = D::NKS * 4096;
     __shared__ __align__(16) bf16_t Q0[TS], Q1[TS], O0[TS], O1[TS];
@@ -341,12 +345,14 @@ __global__ __launch_bounds__(256) void attn_bwd_dkv_mfma_kernel(const bf16_t *__
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int lrow = lane & 31, half = lane >> 5;
     // earliest key blocks (most query tiles under a causal mask) of all heads and sequences first
-    const int per = nkv * n_seqs;
-    const int g = (blockIdx.x % per) % nkv, b = (blockIdx.x % per) / nkv;
+    const int grp = nq / nkv;
+    const int nsub = SPLIT ? grp : 1;
+    const int per = nkv * n_seqs * nsub;
+    const int rem = blockIdx.x % per;
+    const int hsub = rem % nsub, g = (rem / nsub) % nkv, b = rem / (nsub * nkv);
     const int s0 = cu[b], s1 = cu[b + 1];
     const int kblk = (int)(blockIdx.x / per) * BK_;         // first key of the workgroup, relative to s0
     if (kblk >= s1 - s0) return;
-    const int grp = nq / nkv;
     const long ld = (long)(nq + 2 * nkv) * HD, ldo = (long)nq * HD;
     const int key = s0 + kblk + wave * 32 + lrow;           // this lane's key (token index)
     const bool kok = key < s1;
@@ -371,10 +377,10 @@ __global__ __launch_bounds__(256) void attn_bwd_dkv_mfma_kernel(const bf16_t *__
     // query tiles that see this key block
     const int qt_first = CAUSAL ? kblk / BQ : 0;
     const int nqt = (s1 - s0 + BQ - 1) / BQ - qt_first;
-    const int niter = nqt * grp;
+    const int niter = SPLIT ? nqt : nqt * grp;
 
     auto issue = [&](int it, bf16_t *qt_, bf16_t *ot_, float *f) {
-        const int h = g * grp + it / nqt;
+        const int h = g * grp + (SPLIT ? hsub : it / nqt);
         const int qs = s0 + (qt_first + it % nqt) * BQ;
         constexpr int PER = 4 * D::NKS;
 #pragma unroll
@@ -455,12 +461,31 @@ __global__ __launch_bounds__(256) void attn_bwd_dkv_mfma_kernel(const bf16_t *__
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
             const int kk = s0 + kblk + wave * 32 + 8 * (r >> 2) + 4 * half + (r & 3);
-            if (kk < s1) {
+            if (kk >= s1) continue;
+            if constexpr (SPLIT) {
+                float *a = dkv_acc + (long)kk * (2 * nkv * HD) + g * HD + d;
+                unsafeAtomicAdd(a, dk[db][r] * scale);
+                unsafeAtomicAdd(a + nkv * HD, dv[db][r]);
+            } else {
                 dkp[(long)kk * ld + d] = (bf16_t)(dk[db][r] * scale);
                 dvp[(long)kk * ld + d] = (bf16_t)dv[db][r];
             }
         }
     }
+}
+
+// dqkv[:, K and V columns] = bf16(dkv_acc); w = 2 * nkv * HD fp32 per token, 4 per thread
+__global__ __launch_bounds__(256) void attn_dkv_store_kernel(const float *__restrict__ acc, bf16_t *__restrict__ dqkv, long n, int w,
+                                                             long ld, int col0) {
+    const long i = ((long)blockIdx.x * 256 + threadIdx.x) * 4;
+    if (i >= n * w) return;
+    const long t = i / w;
+    const int c = (int)(i % w);
+    const float4 v = *(const float4 *)(acc + i);
+    bf16_t *dst = dqkv + t * ld + col0 + c;
+    union { bf16_t h[4]; uint2 u; } o;
+    o.h[0] = (bf16_t)v.x; o.h[1] = (bf16_t)v.y; o.h[2] = (bf16_t)v.z; o.h[3] = (bf16_t)v.w;
+    *(uint2 *)dst = o.u;
 }
 
 template <int HD>
@@ -488,19 +513,37 @@ ms_status launch_bwd(int causal, int nq, int nkv, int n, int n_seqs, int max_seq
     const long blocks = (long)ntile_max * nq * n_seqs;
     if (blocks > 0x7fffffffL || (long)n * (nq + 2 * nkv) * HD * 2 >= (1L << 32) - (1L << 20))
         return ms_fail(MS_ERR_UNSUPPORTED, "attention: batch too large for 32-bit tile offsets");
-    const unsigned grid_dkv = (unsigned)((long)ntile_max * nkv * n_seqs);
+    // grouped-query attention: split the group's query heads over workgroups (see the kernel)
+    const bool split = nq / nkv > 1;
+    const long blocks_dkv = (long)ntile_max * nkv * n_seqs * (split ? nq / nkv : 1);
+    if (blocks_dkv > 0x7fffffffL) return ms_fail(MS_ERR_UNSUPPORTED, "attention: batch too large for 32-bit tile offsets");
+    const unsigned grid_dkv = (unsigned)blocks_dkv;
+    float *dkv_acc = (float *)((char *)scratch + ms_align_up((size_t)nq * n * sizeof(float)));
+    const int w = 2 * nkv * HD;
+    if (split) MS_TRY(launch_fill_f32(dkv_acc, (long)n * w, 0.f, s));
 #define GO(C)                                                                                                          \
     do {                                                                                                               \
         attn_bwd_dq_mfma_kernel<HD, C><<<(unsigned)blocks, 256, 0, s>>>((const bf16_t *)qkv, (const bf16_t *)d_o, lse, \
                                                                         delta, (bf16_t *)dqkv, cu, n, nq, nkv, n_seqs, \
                                                                         ntile_max, scale);                             \
         MS_LAUNCH_CHECK();                                                                                             \
-        attn_bwd_dkv_mfma_kernel<HD, C><<<grid_dkv, 256, 0, s>>>((const bf16_t *)qkv, (const bf16_t *)d_o, lse, delta, \
-                                                                 (bf16_t *)dqkv, cu, n, nq, nkv, n_seqs, scale);       \
+        if (split)                                                                                                     \
+            attn_bwd_dkv_mfma_kernel<HD, C, true><<<grid_dkv, 256, 0, s>>>((const bf16_t *)qkv, (const bf16_t *)d_o,   \
+                                                                           lse, delta, (bf16_t *)dqkv, dkv_acc, cu, n, \
+                                                                           nq, nkv, n_seqs, scale);                    \
+        else                                                                                                           \
+            attn_bwd_dkv_mfma_kernel<HD, C, false><<<grid_dkv, 256, 0, s>>>((const bf16_t *)qkv, (const bf16_t *)d_o,  \
+                                                                            lse, delta, (bf16_t *)dqkv, dkv_acc, cu,   \
+                                                                            n, nq, nkv, n_seqs, scale);                \
     } while (0)
     if (causal) GO(true); else GO(false);
 #undef GO
     MS_LAUNCH_CHECK();
+    if (split) {
+        attn_dkv_store_kernel<<<ms_cdiv((long)n * w / 4, 256), 256, 0, s>>>(dkv_acc, (bf16_t *)dqkv, n, w, (long)(nq + 2 * nkv) * HD,
+                                                                          nq * HD);
+        MS_LAUNCH_CHECK();
+    }
     return MS_OK;
 }
 
@@ -518,7 +561,10 @@ ms_status attn_mfma_forward(int causal, int nq, int nkv, int hd, int n, int n_se
     return ms_fail(MS_ERR_UNSUPPORTED, "attention: head_dim %d has no matrix-core kernel", hd);
 }
 
-size_t attn_mfma_backward_scratch_bytes(int nq, int, int, int n) { return ms_align_up((size_t)nq * n * sizeof(float)); }
+size_t attn_mfma_backward_scratch_bytes(int nq, int nkv, int hd, int n) {
+    // delta [nq][n], then (grouped-query attention only) the fp32 dK/dV accumulator [n][2][nkv * hd]
+    return ms_align_up((size_t)nq * n * sizeof(float)) + (nq > nkv ? ms_align_up((size_t)n * 2 * nkv * hd * sizeof(float)) : 0);
+}
 
 ms_status attn_mfma_backward(int causal, int nq, int nkv, int hd, int n, int n_seqs, int max_seqlen, const int *cu,
                              const void *qkv, const void *o, const float *lse, const void *d_o, void *dqkv,
