@@ -35,6 +35,8 @@ def build(verbose=True):
                        capture_output=True, text=True)
     if r.returncode != 0:
         raise RuntimeError("link failed:\n" + r.stderr)
+    import ctypes
+    ctypes.CDLL(OUT)   # an unresolved symbol must fail the build, not the first caller
     if verbose:
         print("built", OUT)
     return OUT

@@ -19,6 +19,8 @@
 #include "common.h"
 #include "launch.h"
 #include "mfma_tiles.h"
+#include <type_traits>
+#include <utility>
 
 namespace {
 
@@ -162,6 +164,35 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmParams p) {
 //     past M are dropped by the range check and columns past N by one select per column:
 //     no per-element branches.
 // Needs K % 64 == 0 when an operand is K-contiguous and every matrix below 4 GB.
+// The same for an operand stored K-major: the tile is 64 k-rows x COLS columns, kept as COLS/64 sub-tiles
+// [64][64]; instruction idx fills 8-row group idx % 8 of sub-tile idx / 8.  Rows past K fall outside the
+// descriptor (zeros), so K needs no padding; columns past the matrix edge read the next row (never stored).
+template <int COLS, int NWAVES>
+struct RowTileStager {
+    static constexpr int NI = COLS / 8 / NWAVES;
+    unsigned base[NI];                     // byte offset of this lane's 16 bytes at k0 = 0, per instruction
+    unsigned ldb;                          // bytes per k-row
+    __device__ __forceinline__ void init(long ld, int col0, int wave, int lane) {
+        ldb = (unsigned)(ld * 2);
+#pragma unroll
+        for (int i = 0; i < NI; ++i) {
+            const int idx = wave * NI + i, sub = idx >> 3, g = idx & 7;
+            const int r = g * 8 + (lane >> 3);
+            const int c = (lane & 7) ^ (lane >> 3) ^ (g & 3);
+            base[i] = (unsigned)r * ldb + (unsigned)(col0 + sub * 64 + c * 8) * 2;
+        }
+    }
+    __device__ __forceinline__ void issue(__amdgpu_buffer_rsrc_t rs, bf16_t *tile, int k0, int wave, unsigned inv) const {
+        const unsigned koff = (unsigned)k0 * ldb;
+#pragma unroll
+        for (int i = 0; i < NI; ++i) {
+            const int idx = wave * NI + i;
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(rs, (lds_void *)(tile + (idx >> 3) * 4096 + (idx & 7) * 512), 16,
+                                                     (base[i] + koff) | inv, 0, 0, 0);
+        }
+    }
+};
+
 template <int ROWS, int NWAVES>
 struct DmaStager {
     static constexpr int NI = ROWS / 8 / NWAVES;   // instructions per wave per tile
@@ -174,16 +205,36 @@ struct DmaStager {
         x = (lane & 7) ^ (lane >> 3);
     }
     // wave (scalar) fills 8-row groups wave*NI .. wave*NI + NI-1 of the tile
-    // valid == false fills the tile with zeros (every lane out of range)
-    __device__ __forceinline__ void issue(__amdgpu_buffer_rsrc_t rs, bf16_t *tile, int k0, int wave, bool valid) const {
+    // inv = 0, or kOob to fill the tile with zeros (OR-ing it in puts every lane out of range without a branch)
+    __device__ __forceinline__ void issue(__amdgpu_buffer_rsrc_t rs, bf16_t *tile, int k0, int wave, unsigned inv) const {
 #pragma unroll
         for (int i = 0; i < NI; ++i) {
             const int g = wave * NI + i;
-            const unsigned voff = valid ? rowoff + g * ld8 + ((x ^ (g & 3)) << 4) : kOob;
+            const unsigned voff = (rowoff + g * ld8 + ((x ^ (g & 3)) << 4)) | inv;
             __builtin_amdgcn_raw_ptr_buffer_load_lds(rs, (lds_void *)(tile + g * 8 * BK), 16, voff, k0 * 2, 0, 0);
         }
     }
 };
+
+// Scheduling pattern of one k-step: spread R LDS reads over the first MFMAs (R/M each, at least one),
+// then the remaining MFMAs back to back.
+template <int N>
+__device__ __forceinline__ void sched_reads_then_mfma() {
+    __builtin_amdgcn_sched_group_barrier(0x100, N, 0);   // N LDS reads
+    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);   // one MFMA
+}
+template <int R, int PER, int... I>
+__device__ __forceinline__ void sched_pairs(std::integer_sequence<int, I...>) {
+    (sched_reads_then_mfma<((I + 1) * PER <= R ? PER : R - I * PER)>(), ...);
+}
+template <int R, int M>
+__device__ __forceinline__ void interleave_reads_with_mfma() {
+    constexpr int PER = R >= M ? (R + M - 1) / M : 1;     // reads in front of each of the first MFMAs
+    constexpr int PAIRS = (R + PER - 1) / PER;
+    static_assert(PAIRS <= M, "more read groups than MFMAs");
+    sched_pairs<R, PER>(std::make_integer_sequence<int, PAIRS>{});
+    if constexpr (M > PAIRS) __builtin_amdgcn_sched_group_barrier(0x008, M - PAIRS, 0);
+}
 
 template <int BM, int BN, int WM, int WN, bool TA, bool TB>
 __global__ __launch_bounds__(64 * WM * WN) void gemm_bf16_fast_kernel(GemmParams p) {
@@ -219,13 +270,13 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_bf16_fast_kernel(GemmParams
     if (nk <= 0) return;
 
     const bf16_t *A = (const bf16_t *)p.A, *B = (const bf16_t *)p.B;
-    DmaStager<BM, WM * WN> da;        // used only when !TA
-    DmaStager<BN, WM * WN> db;
+    std::conditional_t<TA, RowTileStager<BM, WM * WN>, DmaStager<BM, WM * WN>> da;
+    std::conditional_t<TB, RowTileStager<BN, WM * WN>, DmaStager<BN, WM * WN>> db;
     // descriptor ranges: rows x leading dimension of the matrix as stored ([M or N][K], or [K][M or N])
     const __amdgpu_buffer_rsrc_t ra = make_rsrc(A, TA ? ((long)(p.K - 1) * p.lda + p.M) * 2 : ((long)(p.M - 1) * p.lda + p.K) * 2);
     const __amdgpu_buffer_rsrc_t rb = make_rsrc(B, TB ? ((long)(p.K - 1) * p.ldb + p.N) * 2 : ((long)(p.N - 1) * p.ldb + p.K) * 2);
-    if constexpr (!TA) da.init(p.lda, m0, lane);
-    if constexpr (!TB) db.init(p.ldb, n0, lane);
+    if constexpr (TA) da.init(p.lda, m0, wave, lane); else da.init(p.lda, m0, lane);
+    if constexpr (TB) db.init(p.ldb, n0, wave, lane); else db.init(p.ldb, n0, lane);
 
     f32x16 acc[MI][NI];
 #pragma unroll
@@ -240,65 +291,76 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_bf16_fast_kernel(GemmParams
     // through the transposing LDS load, so every layout goes global -> LDS without staging registers.
     auto fetch = [&](int kt, bf16_t *as, bf16_t *bs) {
         const bool valid = kt < nk;
+        const unsigned inv = valid ? 0u : kOob;
         const int k0 = (kt_begin + kt) * BK;
-        constexpr int PA = BM / 8 / (WM * WN), PB = BN / 8 / (WM * WN);
-        if constexpr (TA) {
-#pragma unroll
-            for (int i = 0; i < PA; ++i) rowtile_dma<BM>(ra, as, k0, p.lda, m0, wave * PA + i, lane, valid);
-        } else {
-            da.issue(ra, as, k0, wave, valid);
-        }
-        if constexpr (TB) {
-#pragma unroll
-            for (int i = 0; i < PB; ++i) rowtile_dma<BN>(rb, bs, k0, p.ldb, n0, wave * PB + i, lane, valid);
-        } else {
-            db.issue(rb, bs, k0, wave, valid);
-        }
+        da.issue(ra, as, k0, wave, inv);
+        db.issue(rb, bs, k0, wave, inv);
     };
     const int frow = lane & 31, fhalf = lane >> 5;
-    auto compute = [&](const bf16_t *as, const bf16_t *bs) {
-        bf16x8 af[2][MI], bfr[2][NI];
-        // when either operand is K-major both use its k-slot order (two 8-byte reads for the other one)
-        auto load_frags = [&](int kk, int slot) {
+    // 32-row block i (32-column block j) of this wave within the tile.  For a K-major operand the blocks
+    // of a wave are spread one per 64-wide LDS sub-tile pair so that all of them share one LDS address
+    // register (constant offsets); for a K-contiguous operand they are adjacent for the same reason.
+    auto row_base = [&](int i) { return TA ? i * (32 * WM) + wm * 32 : wm * WTM + i * 32; };
+    auto col_base = [&](int j) { return TB ? j * (32 * WN) + wn * 32 : wn * WTN + j * 32; };
+    // Operand fragments are double-buffered in registers: the LDS reads of k-step kk+1 are issued between
+    // the MFMAs of k-step kk.
+    bf16x8 af[2][MI], bfr[2][NI];
+    TrFragAddr tra, trb;
+    if constexpr (TA) tra.init(wm, lane);     // block i of the wave: columns i * 32 * WM + wm * 32 of the row tile
+    if constexpr (TB) trb.init(wn, lane);
+    auto load_frags = [&](const bf16_t *as, const bf16_t *bs, int kk, int slot) {
 #pragma unroll
-            for (int i = 0; i < MI; ++i) {
-                const int row = wm * WTM + i * 32;
-                if constexpr (TA) af[slot][i] = rowtile_tr_frag(as, kk * 16, row, lane);
-                else if constexpr (TB) af[slot][i] = ktile_frag_paired(as, row + frow, kk, fhalf);
-                else af[slot][i] = *(const bf16x8 *)(as + lds_off(row + frow, kk * 2 + fhalf));
-            }
-#pragma unroll
-            for (int j = 0; j < NI; ++j) {
-                const int row = wn * WTN + j * 32;
-                if constexpr (TB) bfr[slot][j] = rowtile_tr_frag(bs, kk * 16, row, lane);
-                else if constexpr (TA) bfr[slot][j] = ktile_frag_paired(bs, row + frow, kk, fhalf);
-                else bfr[slot][j] = *(const bf16x8 *)(bs + lds_off(row + frow, kk * 2 + fhalf));
-            }
-        };
-        load_frags(0, 0);
-#pragma unroll
-        for (int kk = 0; kk < BK / 16; ++kk) {
-            if (kk + 1 < BK / 16) load_frags(kk + 1, (kk + 1) & 1);
-#pragma unroll
-            for (int i = 0; i < MI; ++i)
-#pragma unroll
-                for (int j = 0; j < NI; ++j)
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[kk & 1][i], bfr[kk & 1][j], acc[i][j], 0, 0, 0);
+        for (int i = 0; i < MI; ++i) {
+            const int row = row_base(i);
+            if constexpr (TA) af[slot][i] = tra.frag(as, kk, i * (32 * WM / 64) * 4096);
+            else af[slot][i] = *(const bf16x8 *)(as + lds_off(row + frow, kk * 2 + fhalf));
         }
+#pragma unroll
+        for (int j = 0; j < NI; ++j) {
+            const int row = col_base(j);
+            if constexpr (TB) bfr[slot][j] = trb.frag(bs, kk, j * (32 * WN / 64) * 4096);
+            else bfr[slot][j] = *(const bf16x8 *)(bs + lds_off(row + frow, kk * 2 + fhalf));
+        }
+    };
+    auto mfma_step = [&](int slot) {
+#pragma unroll
+        for (int i = 0; i < MI; ++i)
+#pragma unroll
+            for (int j = 0; j < NI; ++j)
+                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[slot][i], bfr[slot][j], acc[i][j], 0, 0, 0);
+    };
+    constexpr int LDS_READS = (TA ? 2 : 1) * MI + (TB ? 2 : 1) * NI, MFMAS = MI * NI;
+    // One K tile: steps 0..2 read the next step's fragments from the same tile; before the last step the
+    // next tile has landed (own loads: vmcnt(0); the other waves': barrier) and everybody is done reading
+    // this one, so its buffers are handed to the tile after next and the last step reads the first
+    // fragments of the next tile.  One barrier per tile.
+    auto tile = [&](const bf16_t *ca, const bf16_t *cb, const bf16_t *na, const bf16_t *nb, bf16_t *fa, bf16_t *fb, int kt_fetch) {
+#pragma unroll
+        for (int kk = 0; kk < BK / 16 - 1; ++kk) {
+            load_frags(ca, cb, kk + 1, (kk + 1) & 1);
+            mfma_step(kk & 1);
+            interleave_reads_with_mfma<LDS_READS, MFMAS>();
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        __syncthreads();
+        fetch(kt_fetch, fa, fb);
+        load_frags(na, nb, 0, 0);
+        mfma_step((BK / 16 - 1) & 1);
+        interleave_reads_with_mfma<LDS_READS, MFMAS>();
+        __builtin_amdgcn_sched_barrier(0);
     };
 
     fetch(0, As0, Bs0);
     __syncthreads();
+    fetch(1, As1, Bs1);
+    load_frags(As0, Bs0, 0, 0);
     // two K tiles per trip so that each half names its LDS buffers statically; an odd tile count is
     // rounded up with a tile of zeros (a single loop exit keeps the accumulators in place)
     for (int kt = 0; kt < nk; kt += 2) {
-        fetch(kt + 1, As1, Bs1);
-        compute(As0, Bs0);
-        __syncthreads();
-        if (kt + 2 < nk) fetch(kt + 2, As0, Bs0);
-        compute(As1, Bs1);
-        __syncthreads();
+        tile(As0, Bs0, As1, Bs1, As0, Bs0, kt + 2);
+        tile(As1, Bs1, As0, Bs0, As1, Bs1, kt + 3);
     }
+    __syncthreads();   // the (all-zero) tiles still in flight must land before the epilogue reuses LDS
 
     // ---- epilogue.  C and the residual are addressed through buffer descriptors: rows past M are
     // dropped (stores) or read as zero by the range check, columns past N by one select.
@@ -315,7 +377,7 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_bf16_fast_kernel(GemmParams
         constexpr int WPA = BM / 64;                       // waves sharing one of the (now idle) A buffers
         float *stg = (float *)((wave / WPA) ? As1 : As0) + (wave % WPA) * 2048;
         const int prow = lane >> 4, pcol = (lane & 15) * 4;
-        const int colg = n0 + wn * WTN + pcol;
+        const int colg = n0 + col_base(pcol >> 5) + (pcol & 31);
         const bool cok = colg < p.N;
         float bv[4] = {0.f, 0.f, 0.f, 0.f};
         if (bias && cok) {
@@ -341,7 +403,7 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_bf16_fast_kernel(GemmParams
                 const int row = ps * 4 + prow;
                 const float4 t = *(const float4 *)(stg + row * 64 + (pcol ^ (((row >> 2) & 1) << 5)));
                 float v[4] = {t.x + bv[0], t.y + bv[1], t.z + bv[2], t.w + bv[3]};
-                const long rowg = m0 + wm * WTM + i * 32 + row;
+                const long rowg = m0 + row_base(i) + row;
                 if (p.residual) {
                     const unsigned ro = cok ? (unsigned)((rowg * p.ldr + colg) * rsz) : kOob;
                     if (p.res_fp32) {
@@ -380,14 +442,14 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_bf16_fast_kernel(GemmParams
     // scalar epilogue: split-K atomics and shapes whose rows are not 4-element aligned
 #pragma unroll
     for (int j = 0; j < NI; ++j) {
-        const int col = n0 + wn * WTN + j * 32 + frow;
+        const int col = n0 + col_base(j) + frow;
         const bool cok = col < p.N;
         const float bv = (bias && cok) ? (float)bias[col] : 0.f;
 #pragma unroll
         for (int i = 0; i < MI; ++i) {
 #pragma unroll
             for (int r = 0; r < 16; ++r) {
-                const int row = m0 + wm * WTM + i * 32 + 8 * (r >> 2) + 4 * fhalf + (r & 3);
+                const int row = m0 + row_base(i) + 8 * (r >> 2) + 4 * fhalf + (r & 3);
                 float v = acc[i][j][r] * p.alpha + bv;
                 if (p.residual) {
                     const unsigned ro = cok ? (unsigned)(((long)row * p.ldr + col) * rsz) : kOob;
@@ -462,6 +524,13 @@ __global__ __launch_bounds__(256) void gemm_f32_kernel(GemmF32Params p) {
             *c = p.accumulate ? *c + v : v;
         }
 }
+
+// Explicit instantiations: the host pass has been seen to reference the launch stubs of some of these
+// without defining them when they are only instantiated implicitly from the launcher below.
+#define MS_INST(BM, WN, TA, TB) template __global__ void gemm_bf16_fast_kernel<BM, BM, 2, WN, TA, TB>(GemmParams)
+MS_INST(256, 4, false, false); MS_INST(256, 4, false, true); MS_INST(256, 4, true, false); MS_INST(256, 4, true, true);
+MS_INST(128, 2, false, false); MS_INST(128, 2, false, true); MS_INST(128, 2, true, false); MS_INST(128, 2, true, true);
+#undef MS_INST
 
 template <int BM, int BN, int WM, int WN>
 ms_status launch_bf16_fast(const GemmParams &p, int ta, int tb, int splits, hipStream_t s) {

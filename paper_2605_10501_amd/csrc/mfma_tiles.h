@@ -44,12 +44,12 @@ __device__ __forceinline__ bf16x8 tr_frag(const bf16_t *p0, const bf16_t *p1) {
 // arrive as zeros; rows past the end of the matrix are zeroed by the descriptor's range check.
 template <int W>
 __device__ __forceinline__ void rowtile_dma(__amdgpu_buffer_rsrc_t rs, bf16_t *tile, int row0, long ld, int col0, int idx,
-                                            int lane, bool valid = true) {
+                                            int lane, unsigned inv = 0) {
     const int sub = idx >> 3, g = idx & 7;
     const int r = g * 8 + (lane >> 3);
     const int c = (lane & 7) ^ (lane >> 3) ^ (g & 3);
     const int d = sub * 64 + c * 8;
-    const unsigned voff = (valid && d < W) ? (unsigned)(((long)(row0 + r) * ld + col0 + d) * 2) : kOob;
+    const unsigned voff = (d < W ? (unsigned)(((long)(row0 + r) * ld + col0 + d) * 2) : kOob) | inv;   // inv = kOob: all zeros
     __builtin_amdgcn_raw_ptr_buffer_load_lds(rs, (lds_void *)(tile + sub * 4096 + g * 512), 16, voff, 0, 0, 0);
 }
 
@@ -64,15 +64,40 @@ __device__ __forceinline__ bf16x8 rowtile_tr_frag(const bf16_t *tile, int k0, in
     return tr_frag(base + lds_off(row, chunk), base + lds_off(row + 8, chunk));
 }
 
-// Fragment of a K-contiguous tile [rows][64] with the SAME k-slot order as rowtile_tr_frag (for MFMAs
-// that pair one operand of each kind): two 8-byte reads instead of one 16-byte read.
-__device__ __forceinline__ bf16x8 ktile_frag_paired(const bf16_t *tile, int row, int kk, int half) {
-    const uint2 lo = *(const uint2 *)(tile + lds_off(row, kk * 2) + 4 * half);
-    const uint2 hi = *(const uint2 *)(tile + lds_off(row, kk * 2 + 1) + 4 * half);
-    union { uint4 u; bf16x8 v; } f;
-    f.u = make_uint4(lo.x, lo.y, hi.x, hi.y);
-    return f.v;
+// Same, in the standard k-slot order of a K-contiguous fragment: half h gets rows k0 + 8h + {0..7}, so it
+// pairs with 16-byte reads of the other operand.
+__device__ __forceinline__ bf16x8 rowtile_tr_frag_std(const bf16_t *tile, int k0, int m0, int lane) {
+    const int h = lane >> 5, dg = (lane >> 4) & 1, r = lane & 15;
+    const int row = k0 + 8 * h + (r >> 2);
+    const int m = m0 + 16 * dg + 4 * (r & 3);
+    const bf16_t *base = tile + (m >> 6) * 4096 + (m & 7);
+    const int chunk = (m & 63) >> 3;
+    return tr_frag(base + lds_off(row, chunk), base + lds_off(row + 4, chunk));
 }
+
+// Addresses of rowtile_tr_frag_std for one wave, factored so that only four registers per operand are
+// live: the swizzle term depends on the k-step's parity alone, everything else is a constant offset.
+// The wave's 32-column blocks start at column w32 * 32 of sub-tile pairs that the caller selects with
+// a constant element offset (multiples of 4096).
+struct TrFragAddr {
+    int base[2][2];   // [k-step parity][first / second read], element offset within the tile
+    __device__ __forceinline__ void init(int w32, int lane) {
+        const int h = lane >> 5, dg = (lane >> 4) & 1, r = lane & 15, q = r >> 2;
+        const int m = w32 * 32 + 16 * dg + 4 * (r & 3);
+        const int sub = m >> 6, chunk = (m & 63) >> 3;
+#pragma unroll
+        for (int par = 0; par < 2; ++par)
+#pragma unroll
+            for (int rd = 0; rd < 2; ++rd) {
+                const int rl = 8 * h + q + 4 * rd;                       // row within the 16-row k-step
+                const int sw = (rl & 7) ^ ((2 * par + h) & 3);
+                base[par][rd] = sub * 4096 + rl * 64 + ((chunk ^ sw) << 3) + (m & 7);
+            }
+    }
+    __device__ __forceinline__ bf16x8 frag(const bf16_t *tile, int kk, int off) const {
+        return tr_frag(tile + base[kk & 1][0] + kk * 1024 + off, tile + base[kk & 1][1] + kk * 1024 + off);
+    }
+};
 
 __device__ __forceinline__ uint32_t pack_lo(uint32_t a, uint32_t b) { return (a & 0xffffu) | (b << 16); }
 __device__ __forceinline__ uint32_t pack_hi(uint32_t a, uint32_t b) { return (a >> 16) | (b & 0xffff0000u); }
