@@ -29,7 +29,7 @@ __device__ __forceinline__ bf16x8 pack8(const float *v) {
 }
 
 template <int HD, bool CAUSAL>
-__global__ __launch_bounds__(256) void attn_fwd_mfma_kernel(const bf16_t *__restrict__ qkv, bf16_t *__restrict__ o,
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) void attn_fwd_mfma_kernel(const bf16_t *__restrict__ qkv, bf16_t *__restrict__ o,
                                                              float *__restrict__ lse, const int *__restrict__ cu, int n,
                                                              int nq, int nkv, int n_seqs, int ntile_max, float scale_log2e) {
     using D = AttnDims<HD>;
@@ -98,30 +98,37 @@ __global__ __launch_bounds__(256) void attn_fwd_mfma_kernel(const bf16_t *__rest
                 st[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[ks], st[kb], 0, 0, 0);
             }
         }
-        // scale, mask, row maximum (one query per lane; the other half-wave holds the other keys)
+        // mask (only tiles that touch the diagonal or the end of the sequence: wave-uniform test), row
+        // maximum on the raw scores (one query per lane; the other half-wave holds the other keys),
+        // then p = exp2(s * scale - m) with the scale folded into one fused multiply-add
         const int key0 = s0 + j * BKV + 4 * half;
-        float p[2][16];
+        const bool need_mask = s0 + j * BKV + BKV > kv_end || (CAUSAL && s0 + j * BKV + BKV - 1 > q0);
+        if (need_mask) {
+#pragma unroll
+            for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    const int key = key0 + kb * 32 + 8 * (r >> 2) + (r & 3);
+                    const bool ok = key < kv_end && (!CAUSAL || key <= q);
+                    st[kb][r] = ok ? st[kb][r] : -INFINITY;
+                }
+        }
         float mx = -INFINITY;
 #pragma unroll
         for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const int key = key0 + kb * 32 + 8 * (r >> 2) + (r & 3);
-                const bool ok = key < kv_end && (!CAUSAL || key <= q);
-                const float s = ok ? st[kb][r] * scale_log2e : -INFINITY;
-                p[kb][r] = s;
-                mx = fmaxf(mx, s);
-            }
-        mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+            for (int r = 0; r < 16; ++r) mx = fmaxf(mx, st[kb][r]);
+        mx = fmaxf(mx, __shfl_xor(mx, 32, 64)) * scale_log2e;
         const float m_new = fmaxf(m, mx);
         const float m_use = m_new == -INFINITY ? 0.f : m_new;
         const float alpha = __builtin_amdgcn_exp2f(m - m_use);          // m = -inf on the first tile -> 0
+        float p[2][16];
         float psum = 0.f;
 #pragma unroll
         for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
             for (int r = 0; r < 16; ++r) {
-                p[kb][r] = __builtin_amdgcn_exp2f(p[kb][r] - m_use);
+                p[kb][r] = __builtin_amdgcn_exp2f(__builtin_fmaf(st[kb][r], scale_log2e, -m_use));
                 psum += p[kb][r];
             }
         l = l * alpha + psum;
