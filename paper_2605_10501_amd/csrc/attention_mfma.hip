@@ -9,6 +9,8 @@
 // layout a lane then holds 32 keys of ONE query, so the online-softmax row maximum and sum are
 // register reductions plus a single cross-half shuffle, the rescale factor is a per-lane scalar,
 // and the probabilities are already laid out as the B operand of O^T += Vt P^T.
+#include <type_traits>
+
 #include "attention.h"
 #include "launch.h"
 #include "mfma_tiles.h"
@@ -208,7 +210,7 @@ __global__ __launch_bounds__(256) void attn_delta_kernel(const bf16_t *__restric
 // dS^T = P (dP^T - delta[q]) use per-lane scalars, and dS^T is the B operand of dQ^T += K^T dS^T
 // with K^T read from the row-major K tile through the transposing LDS load.
 template <int HD, bool CAUSAL>
-__global__ __launch_bounds__(256) void attn_bwd_dq_mfma_kernel(const bf16_t *__restrict__ qkv, const bf16_t *__restrict__ d_o,
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) void attn_bwd_dq_mfma_kernel(const bf16_t *__restrict__ qkv, const bf16_t *__restrict__ d_o,
                                                                 const float *__restrict__ lse, const float *__restrict__ delta,
                                                                 bf16_t *__restrict__ dqkv, const int *__restrict__ cu, int n,
                                                                 int nq, int nkv, int n_seqs, int ntile_max, float scale) {
@@ -282,12 +284,17 @@ __global__ __launch_bounds__(256) void attn_bwd_dq_mfma_kernel(const bf16_t *__r
                 st = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*(const bf16x8 *)(kt + off), qf[ks], st, 0, 0, 0);
                 dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*(const bf16x8 *)(vt + off), dof[ks], dp, 0, 0, 0);
             }
+            // rows past the end of the sequence have zero Q, dO, lse and delta (dS = 0 there without a mask)
+            const int kfirst = s0 + j * BKV + kb * 32;
+            const bool need_mask = kfirst + 32 > kv_end || (CAUSAL && kfirst + 31 > q0);
             float ds[16];
 #pragma unroll
             for (int r = 0; r < 16; ++r) {
-                const int key = key0 + kb * 32 + 8 * (r >> 2) + (r & 3);
-                const bool ok = qok && key < kv_end && (!CAUSAL || key <= q);
-                const float p = ok ? __builtin_amdgcn_exp2f(st[r] * c - lse2) : 0.f;
+                float p = __builtin_amdgcn_exp2f(__builtin_fmaf(st[r], c, -lse2));
+                if (need_mask) {
+                    const int key = key0 + kb * 32 + 8 * (r >> 2) + (r & 3);
+                    p = (key < kv_end && (!CAUSAL || key <= q)) ? p : 0.f;
+                }
                 ds[r] = p * (dp[r] - dlt);
             }
 #pragma unroll
@@ -327,26 +334,26 @@ __global__ __launch_bounds__(256) void attn_bwd_dq_mfma_kernel(const bf16_t *__r
         }
 }
 
-// dK, dV: workgroup = 128 keys of one KV head (32 per wave, K and V fragments in registers); it
-// walks the query heads of the group and their query tiles, 64 rows at a time, with the Q and dO
-// tiles loaded directly into LDS.  S = Q K^T and dP = dO V^T are accumulator tiles with one KEY
-// per lane and queries down the registers, which is the A-operand layout of dV += P^T dO and
-// dK += dS^T Q; their B operands (dO and Q with queries as the contraction index) come from the
-// row-major tiles through the transposing LDS load.  The sums over the query group stay in
-// registers: no atomics.
+// dK, dV: workgroup = 128 keys of one KV head (32 per wave; K fragments in registers, the V tile in
+// LDS); it walks the query heads of the group and their query tiles, 32 rows at a time, with the Q
+// and dO tiles loaded directly into LDS (double-buffered).  S = Q K^T and dP = dO V^T are accumulator
+// tiles with one KEY per lane and queries down the registers, which is the A-operand layout of
+// dV += P^T dO and dK += dS^T Q; their B operands (dO and Q with queries as the contraction index)
+// come from the row-major tiles through the transposing LDS load.  Everything fits 256 registers and
+// 66 KB of LDS, so two workgroups share a CU and one's softmax overlaps the other's MFMAs.
+// !SPLIT: the sums over the query group stay in registers, no atomics.
 // SPLIT: one workgroup per query head of the group instead of one per K/V head (4x the workgroups and a 4x
 // shorter longest one under grouped-query attention); partial dK/dV are then summed with fp32 atomics
 // into dkv_acc [n][2][nkv * HD], which attn_dkv_store_kernel rounds into dqkv afterwards.
 template <int HD, bool CAUSAL, bool SPLIT>
-__global__ __launch_bounds__(256) void attn_bwd_dkv_mfma_kernel(const bf16_t *__restrict__ qkv, const bf16_t *__restrict__ d_o,
-                                                                 const float *__restrict__ lse, const float *__restrict__ delta,
-                                                                 bf16_t *__restrict__ dqkv, float *__restrict__ dkv_acc,
-                                                                 const int *__restrict__ cu, int n, int nq, int nkv,
-                                                                 int n_seqs, float scale) {
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) void attn_bwd_dkv_mfma_kernel(
+    const bf16_t *__restrict__ qkv, const bf16_t *__restrict__ d_o, const float *__restrict__ lse, const float *__restrict__ delta,
+    bf16_t *__restrict__ dqkv, float *__restrict__ dkv_acc, const int *__restrict__ cu, int n, int nq, int nkv, int n_seqs,
+    float scale) {
     using D = AttnDims<HD>;
-    constexpr int BK_ = 128, BQ = 64, TS = D::NKS * 4096;
-    __shared__ __align__(16) bf16_t Q0[TS], Q1[TS], O0[TS], O1[TS];
-    __shared__ __align__(16) float F0[128], F1[128];       // per query row: lse * log2(e) | delta
+    constexpr int BK_ = 128, BQ = 32, QS = D::NKS * 2048, VS = D::NKS * 4096;
+    __shared__ __align__(16) bf16_t Q0[QS], Q1[QS], O0[QS], O1[QS], Vs[2 * VS];
+    __shared__ __align__(16) float F0[64], F1[64];         // per query row: lse * log2(e) | delta
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -361,24 +368,31 @@ __global__ __launch_bounds__(256) void attn_bwd_dkv_mfma_kernel(const bf16_t *__
     const int kblk = (int)(blockIdx.x / per) * BK_;         // first key of the workgroup, relative to s0
     if (kblk >= s1 - s0) return;
     const long ld = (long)(nq + 2 * nkv) * HD, ldo = (long)nq * HD;
-    const int key = s0 + kblk + wave * 32 + lrow;           // this lane's key (token index)
+    const int kw0 = s0 + kblk + wave * 32;                  // first key of the wave
+    const int key = kw0 + lrow;                             // this lane's key (token index)
     const bool kok = key < s1;
     const float c = scale * 1.4426950408889634f;
     const __amdgpu_buffer_rsrc_t rq = make_rsrc(qkv, (long)n * ld * 2), ro = make_rsrc(d_o, (long)n * ldo * 2);
 
-    bf16x8 kf[D::KST], vf[D::KST];
+    // the V tile (two 64-key row tiles): keys past the end of the sequence hold the next sequence's rows
+    // or zeros, which only ever meet p = 0
+    {
+        constexpr int PER = 4 * D::NKS;                     // 2 * 8 * NKS instructions over 4 waves
+#pragma unroll
+        for (int i = 0; i < PER; ++i) {
+            const int idx = wave * PER + i, t = idx / (8 * D::NKS);
+            rowtile_dma<HD>(rq, Vs + t * VS, s0 + kblk + t * 64, ld, (nq + nkv + g) * HD, idx % (8 * D::NKS), lane);
+        }
+    }
+    bf16x8 kf[D::KST];
     {
         const bf16_t *kp = qkv + (long)key * ld + (long)(nq + g) * HD + half * 8;
-        const bf16_t *vp = qkv + (long)key * ld + (long)(nq + nkv + g) * HD + half * 8;
 #pragma unroll
         for (int ks = 0; ks < D::KST; ++ks) {
-            if (kok) {
-                kf[ks] = *(const bf16x8 *)(kp + ks * 16);
-                vf[ks] = *(const bf16x8 *)(vp + ks * 16);
-            } else {
+            if (kok) kf[ks] = *(const bf16x8 *)(kp + ks * 16);
+            else
 #pragma unroll
-                for (int i = 0; i < 8; ++i) { kf[ks][i] = (bf16_t)0.f; vf[ks][i] = (bf16_t)0.f; }
-            }
+                for (int i = 0; i < 8; ++i) kf[ks][i] = (bf16_t)0.f;
         }
     }
     // query tiles that see this key block
@@ -389,96 +403,110 @@ __global__ __launch_bounds__(256) void attn_bwd_dkv_mfma_kernel(const bf16_t *__
     auto issue = [&](int it, bf16_t *qt_, bf16_t *ot_, float *f) {
         const int h = g * grp + (SPLIT ? hsub : it / nqt);
         const int qs = s0 + (qt_first + it % nqt) * BQ;
-        constexpr int PER = 4 * D::NKS;
+        constexpr int PER = 2 * D::NKS;                     // 2 * 4 * NKS instructions over 4 waves
 #pragma unroll
         for (int i = 0; i < PER; ++i) {
             const int idx = wave * PER + i;
-            if (idx < 8 * D::NKS) rowtile_dma<HD>(rq, qt_, qs, ld, h * HD, idx, lane);
-            else rowtile_dma<HD>(ro, ot_, qs, ldo, h * HD, idx - 8 * D::NKS, lane);
+            if (idx < 4 * D::NKS) rowtile32_dma<HD>(rq, qt_, qs, ld, h * HD, idx, lane);
+            else rowtile32_dma<HD>(ro, ot_, qs, ldo, h * HD, idx - 4 * D::NKS, lane);
         }
-        if (tid < 64) f[tid] = qs + tid < s1 ? lse[(long)h * n + qs + tid] * 1.4426950408889634f : 0.f;
-        else if (tid < 128) f[tid] = qs + tid - 64 < s1 ? delta[(long)h * n + qs + tid - 64] : 0.f;
+        if (tid < 32) f[tid] = qs + tid < s1 ? lse[(long)h * n + qs + tid] * 1.4426950408889634f : 0.f;
+        else if (tid < 64) f[tid] = qs + tid - 32 < s1 ? delta[(long)h * n + qs + tid - 32] : 0.f;
     };
 
-    f32x16 dk[D::DB], dv[D::DB];
-#pragma unroll
-    for (int i = 0; i < D::DB; ++i)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) { dk[i][r] = 0.f; dv[i][r] = 0.f; }
-
-    auto compute = [&](int it, const bf16_t *qt_, const bf16_t *ot_, const float *f) {
-        const float *ls = f, *dl = f + 64;
+    const bf16_t *vrow = Vs + (wave >> 1) * VS;             // the 64-key row tile holding this wave's keys
+    const int vr = (wave & 1) * 32 + lrow;
+    // One pass over the query tiles accumulates dV (WHICH = 0: needs S only) or dK (WHICH = 1: needs S
+    // and dP).  Two passes cost one extra S product per tile but halve the accumulators, which is what
+    // lets two workgroups share a CU.
+    f32x16 acc[D::DB];
+    auto compute = [&](auto which, int it, const bf16_t *qt_, const bf16_t *ot_, const float *f) __attribute__((always_inline)) {
+        constexpr bool DK = decltype(which)::value;
+        const float *ls = f, *dl = f + 32;
         const int qs = s0 + (qt_first + it % nqt) * BQ;
+        if (CAUSAL && qs + BQ - 1 < kw0) return;            // every query of the tile precedes every key of the wave
+        f32x16 st, dp;
 #pragma unroll
-        for (int qb = 0; qb < 2; ++qb) {
-            f32x16 st, dp;
+        for (int r = 0; r < 16; ++r) { st[r] = 0.f; dp[r] = 0.f; }
 #pragma unroll
-            for (int r = 0; r < 16; ++r) { st[r] = 0.f; dp[r] = 0.f; }
-#pragma unroll
-            for (int ks = 0; ks < D::KST; ++ks) {
-                const int off = (ks / 4) * 4096 + lds_off(qb * 32 + lrow, (ks % 4) * 2 + half);
-                st = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*(const bf16x8 *)(qt_ + off), kf[ks], st, 0, 0, 0);
-                dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*(const bf16x8 *)(ot_ + off), vf[ks], dp, 0, 0, 0);
+        for (int ks = 0; ks < D::KST; ++ks) {
+            const int off = lds_off(lrow, (ks % 4) * 2 + half);
+            st = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*(const bf16x8 *)(qt_ + (ks / 4) * 2048 + off), kf[ks], st, 0, 0, 0);
+            if constexpr (DK) {
+                const bf16x8 vfr = *(const bf16x8 *)(vrow + (ks / 4) * 4096 + lds_off(vr, (ks % 4) * 2 + half));
+                dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*(const bf16x8 *)(ot_ + (ks / 4) * 2048 + off), vfr, dp, 0, 0, 0);
             }
-            // accumulator rows are queries qb*32 + 8*(r/4) + 4*half + r%4, the column is this lane's key
-            float p[16], ds[16];
+        }
+        // accumulator rows are queries 8*(r/4) + 4*half + r%4, the column is this lane's key; rows past
+        // the end of the sequence have zero Q, dO, lse and delta, so only keys need masking there
+        const bool need_mask = kw0 + 31 >= s1 || qs + BQ > s1 || (CAUSAL && kw0 + 31 > qs);
+        // 16 queries (one MFMA k-step of the second product) at a time, to keep few values live
 #pragma unroll
-            for (int rg = 0; rg < 4; ++rg) {
-                const int qr = qb * 32 + 8 * rg + 4 * half;
-                const float4 l4 = *(const float4 *)(ls + qr), d4 = *(const float4 *)(dl + qr);
-                const float lv[4] = {l4.x, l4.y, l4.z, l4.w}, dvv[4] = {d4.x, d4.y, d4.z, d4.w};
+        for (int t = 0; t < 2; ++t) {
+            float w[8];
+#pragma unroll
+            for (int rg = 0; rg < 2; ++rg) {
+                const int qr = 16 * t + 8 * rg + 4 * half;
+                const float4 l4 = *(const float4 *)(ls + qr);
+                const float lv[4] = {l4.x, l4.y, l4.z, l4.w};
+                float dvv[4] = {0.f, 0.f, 0.f, 0.f};
+                if constexpr (DK) {
+                    const float4 d4 = *(const float4 *)(dl + qr);
+                    dvv[0] = d4.x; dvv[1] = d4.y; dvv[2] = d4.z; dvv[3] = d4.w;
+                }
 #pragma unroll
                 for (int e = 0; e < 4; ++e) {
                     const int r = rg * 4 + e;
-                    const int qq = qs + qr + e;
-                    const bool ok = kok && qq < s1 && (!CAUSAL || key <= qq);
-                    p[r] = ok ? __builtin_amdgcn_exp2f(st[r] * c - lv[e]) : 0.f;
-                    ds[r] = p[r] * (dp[r] - dvv[e]);
+                    float pe = __builtin_amdgcn_exp2f(__builtin_fmaf(st[8 * t + r], c, -lv[e]));
+                    if (need_mask) {
+                        const int qq = qs + qr + e;
+                        pe = (kok && qq < s1 && (!CAUSAL || key <= qq)) ? pe : 0.f;
+                    }
+                    w[r] = DK ? pe * (dp[8 * t + r] - dvv[e]) : pe;
                 }
             }
+            const bf16x8 wf = pack8(w);
+            const bf16_t *bt = DK ? qt_ : ot_;              // dK += dS^T Q, dV += P^T dO
 #pragma unroll
-            for (int t = 0; t < 2; ++t) {
-                const bf16x8 pf = pack8(&p[8 * t]), dsf = pack8(&ds[8 * t]);
+            for (int db = 0; db < D::DB; ++db)
+                acc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf, rowtile_tr_frag<2048>(bt, 16 * t, db * 32, lane), acc[db], 0, 0, 0);
+        }
+    };
+    // accumulators: row = key wave*32 + 8*(r/4) + 4*half + r%4, column d = db*32 + lrow
+    auto store = [&](int col0, float mul) __attribute__((always_inline)) {
 #pragma unroll
-                for (int db = 0; db < D::DB; ++db) {
-                    dv[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(pf, rowtile_tr_frag(ot_, qb * 32 + 16 * t, db * 32, lane), dv[db], 0, 0, 0);
-                    dk[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(dsf, rowtile_tr_frag(qt_, qb * 32 + 16 * t, db * 32, lane), dk[db], 0, 0, 0);
-                }
+        for (int db = 0; db < D::DB; ++db) {
+            const int d = db * 32 + lrow;
+            if (d >= HD) continue;
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int kk = s0 + kblk + wave * 32 + 8 * (r >> 2) + 4 * half + (r & 3);
+                if (kk >= s1) continue;
+                if constexpr (SPLIT) unsafeAtomicAdd(dkv_acc + (long)kk * (2 * nkv * HD) + col0 - nq * HD + d, acc[db][r] * mul);
+                else dqkv[(long)kk * ld + col0 + d] = (bf16_t)(acc[db][r] * mul);
             }
         }
     };
-
-    issue(0, Q0, O0, F0);
-    __syncthreads();
-    for (int it = 0; it < niter; it += 2) {
-        if (it + 1 < niter) issue(it + 1, Q1, O1, F1);
-        compute(it, Q0, O0, F0);
-        __syncthreads();
-        if (it + 2 < niter) issue(it + 2, Q0, O0, F0);
-        if (it + 1 < niter) compute(it + 1, Q1, O1, F1);
-        __syncthreads();
-    }
-
-    // accumulators: row = key wave*32 + 8*(r/4) + 4*half + r%4, column d = db*32 + lrow
-    bf16_t *dkp = dqkv + (long)(nq + g) * HD, *dvp = dqkv + (long)(nq + nkv + g) * HD;
+    auto pass = [&](auto which) __attribute__((always_inline)) {
 #pragma unroll
-    for (int db = 0; db < D::DB; ++db) {
-        const int d = db * 32 + lrow;
-        if (d >= HD) continue;
+        for (int i = 0; i < D::DB; ++i)
 #pragma unroll
-        for (int r = 0; r < 16; ++r) {
-            const int kk = s0 + kblk + wave * 32 + 8 * (r >> 2) + 4 * half + (r & 3);
-            if (kk >= s1) continue;
-            if constexpr (SPLIT) {
-                float *a = dkv_acc + (long)kk * (2 * nkv * HD) + g * HD + d;
-                unsafeAtomicAdd(a, dk[db][r] * scale);
-                unsafeAtomicAdd(a + nkv * HD, dv[db][r]);
-            } else {
-                dkp[(long)kk * ld + d] = (bf16_t)(dk[db][r] * scale);
-                dvp[(long)kk * ld + d] = (bf16_t)dv[db][r];
-            }
+            for (int r = 0; r < 16; ++r) acc[i][r] = 0.f;
+        issue(0, Q0, O0, F0);
+        __syncthreads();
+        for (int it = 0; it < niter; it += 2) {
+            if (it + 1 < niter) issue(it + 1, Q1, O1, F1);
+            compute(which, it, Q0, O0, F0);
+            __syncthreads();
+            if (it + 2 < niter) issue(it + 2, Q0, O0, F0);
+            if (it + 1 < niter) compute(which, it + 1, Q1, O1, F1);
+            __syncthreads();
         }
-    }
+    };
+    pass(std::false_type{});
+    store((nq + nkv + g) * HD, 1.f);
+    pass(std::true_type{});
+    store((nq + g) * HD, scale);
 }
 
 // dqkv[:, K and V columns] = bf16(dkv_acc); w = 2 * nkv * HD fp32 per token, 4 per thread

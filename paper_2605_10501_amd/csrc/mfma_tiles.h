@@ -53,13 +53,27 @@ __device__ __forceinline__ void rowtile_dma(__amdgpu_buffer_rsrc_t rs, bf16_t *t
     __builtin_amdgcn_raw_ptr_buffer_load_lds(rs, (lds_void *)(tile + sub * 4096 + g * 512), 16, voff, 0, 0, 0);
 }
 
+// The same for a tile of 32 rows (sub-tiles [32][64]): instruction idx fills 8-row group idx % 4 of sub-tile idx / 4.
+template <int W>
+__device__ __forceinline__ void rowtile32_dma(__amdgpu_buffer_rsrc_t rs, bf16_t *tile, int row0, long ld, int col0, int idx,
+                                              int lane) {
+    const int sub = idx >> 2, g = idx & 3;
+    const int r = g * 8 + (lane >> 3);
+    const int c = (lane & 7) ^ (lane >> 3) ^ g;
+    const int d = sub * 64 + c * 8;
+    const unsigned voff = d < W ? (unsigned)(((long)(row0 + r) * ld + col0 + d) * 2) : kOob;
+    __builtin_amdgcn_raw_ptr_buffer_load_lds(rs, (lds_void *)(tile + sub * 2048 + g * 512), 16, voff, 0, 0, 0);
+}
+
 // MFMA operand fragment whose 32 "rows" are tile columns m0 .. m0+31 and whose k-slots are tile rows:
 // half h of the wave gets rows k0 + 4h + {0..3} (slots 0..3) and k0 + 8 + 4h + {0..3} (slots 4..7).
+// SUB = elements per 64-column sub-tile (64 x tile height).
+template <int SUB = 4096>
 __device__ __forceinline__ bf16x8 rowtile_tr_frag(const bf16_t *tile, int k0, int m0, int lane) {
     const int h = lane >> 5, dg = (lane >> 4) & 1, r = lane & 15;
     const int row = k0 + 4 * h + (r >> 2);
     const int m = m0 + 16 * dg + 4 * (r & 3);
-    const bf16_t *base = tile + (m >> 6) * 4096 + (m & 7);
+    const bf16_t *base = tile + (m >> 6) * SUB + (m & 7);
     const int chunk = (m & 63) >> 3;
     return tr_frag(base + lds_off(row, chunk), base + lds_off(row + 8, chunk));
 }
