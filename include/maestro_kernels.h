@@ -64,7 +64,8 @@ ms_status ms_k_act_forward(int32_t kind, int32_t dtype, int32_t n, int32_t f, co
 ms_status ms_k_act_backward(int32_t kind, int32_t dtype, int32_t n, int32_t f, const void *da,
                             const void *up, void *dup, void *stream);
 
-/* x[t, :] = table[ids[t], :]; out_fp32 != 0 widens a bf16 table row to fp32 on the way. */
+/* x[t, :] = table[ids[t], :]; out_fp32 != 0 widens a bf16 table row to fp32 on the way.  An id outside
+ * [0, vocab) embeds as a row of zeros and receives no gradient (never an out-of-bounds access). */
 ms_status ms_k_embedding_forward(int32_t dtype, int32_t out_fp32, int32_t n, int32_t d, int32_t vocab,
                                  const int32_t *ids, const void *table, void *x, void *stream);
 /* d_table[ids[t], :] += dx[t, :]  (fp32, atomic). */

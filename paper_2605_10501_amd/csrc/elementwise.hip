@@ -200,18 +200,24 @@ __global__ __launch_bounds__(256) void norm_bwd_kernel(const T *__restrict__ dy,
     }
 }
 
-// out[j] += sum_p part[p, j]; block = 64 columns x 4 row lanes.
-__global__ __launch_bounds__(256) void reduce_partials_kernel(const float *__restrict__ part, int np, int c,
-                                                               float *__restrict__ out) {
-    __shared__ float sm[4][64];
-    const int col = blockIdx.x * 64 + (threadIdx.x & 63);
-    const int pl = threadIdx.x >> 6;
+// out[j] += sum_p part[p, j]; block = 32 columns x 32 row lanes (many short dependent-load chains
+// instead of a few long ones: the partial matrix is small and the kernel is latency-bound).
+__global__ __launch_bounds__(1024) void reduce_partials_kernel(const float *__restrict__ part, int np, int c,
+                                                                float *__restrict__ out) {
+    __shared__ float sm[32][33];
+    const int cl = threadIdx.x & 31, pl = threadIdx.x >> 5;
+    const int col = blockIdx.x * 32 + cl;
     float s = 0.f;
     if (col < c)
-        for (int p = pl; p < np; p += 4) s += part[(size_t)p * c + col];
-    sm[pl][threadIdx.x & 63] = s;
+        for (int p = pl; p < np; p += 32) s += part[(size_t)p * c + col];
+    sm[pl][cl] = s;
     __syncthreads();
-    if (pl == 0 && col < c) out[col] += sm[0][threadIdx.x] + sm[1][threadIdx.x] + sm[2][threadIdx.x] + sm[3][threadIdx.x];
+    if (pl == 0 && col < c) {
+        float t = 0.f;
+#pragma unroll
+        for (int i = 0; i < 32; ++i) t += sm[i][cl];
+        out[col] += t;
+    }
 }
 
 // partial column sums: lane <-> one 16-byte column vector, waves stride over rows.
@@ -350,14 +356,19 @@ __global__ __launch_bounds__(256) void act_bwd_kernel(const T *__restrict__ da, 
 // ------------------------------------------------------------------ embedding
 template <class T, class TO>
 __global__ __launch_bounds__(256) void embedding_fwd_kernel(const int *__restrict__ ids, const T *__restrict__ table,
-                                                            TO *__restrict__ x, long nvec_total, int d) {
+                                                            TO *__restrict__ x, long nvec_total, int d, int vocab) {
     constexpr int V = Vec16<T>::N;
     long idx = (long)blockIdx.x * blockDim.x + threadIdx.x;
     if (idx >= nvec_total) return;
     const int vpr = d / V;
     long t = idx / vpr;
     int cv = idx % vpr;
-    const Vec16<T> v = ldv(table + (long)ids[t] * d + (long)cv * V);
+    const int id = ids[t];
+    Vec16<T> v;
+    if ((unsigned)id < (unsigned)vocab) v = ldv(table + (long)id * d + (long)cv * V);
+    else                                  // an id outside the table embeds as zeros: never an out-of-bounds read
+#pragma unroll
+        for (int e = 0; e < V; ++e) v.v[e] = from_f32<T>(0.f);
     TO *o = x + t * d + (long)cv * V;
     if constexpr (sizeof(TO) == sizeof(T)) {
         stv(o, v);
@@ -368,19 +379,17 @@ __global__ __launch_bounds__(256) void embedding_fwd_kernel(const int *__restric
     }
 }
 
+// one workgroup per token; consecutive lanes add to consecutive floats, so that one atomic instruction
+// touches 256 contiguous bytes of the table row
 template <class T>
 __global__ __launch_bounds__(256) void embedding_bwd_kernel(const int *__restrict__ ids, const T *__restrict__ dx,
-                                                            float *__restrict__ dtab, long nvec_total, int d) {
-    constexpr int V = Vec16<T>::N;
-    long idx = (long)blockIdx.x * blockDim.x + threadIdx.x;
-    if (idx >= nvec_total) return;
-    const int vpr = d / V;
-    long t = idx / vpr;
-    int cv = idx % vpr;
-    Vec16<T> v = ldv(dx + t * d + (long)cv * V);
-    float *o = dtab + (long)ids[t] * d + (long)cv * V;
-#pragma unroll
-    for (int e = 0; e < V; ++e) unsafeAtomicAdd(o + e, to_f32(v.v[e]));
+                                                            float *__restrict__ dtab, int d, int vocab) {
+    const long t = blockIdx.x;
+    const T *src = dx + t * d;
+    const int id = ids[t];
+    if ((unsigned)id >= (unsigned)vocab) return;   // an id outside the table receives no gradient
+    float *o = dtab + (long)id * d;
+    for (int c = threadIdx.x; c < d; c += 256) unsafeAtomicAdd(o + c, to_f32(src[c]));
 }
 
 // ------------------------------------------------------------------ fills / conversions
@@ -446,7 +455,7 @@ extern "C" size_t ms_k_norm_backward_scratch_bytes(int32_t d) {
 }
 
 static ms_status reduce_partials(const float *part, int np, int c, float *out, hipStream_t s) {
-    reduce_partials_kernel<<<ms_cdiv(c, 64), 256, 0, s>>>(part, np, c, out);
+    reduce_partials_kernel<<<ms_cdiv(c, 32), 1024, 0, s>>>(part, np, c, out);
     MS_LAUNCH_CHECK();
     return MS_OK;
 }
@@ -570,9 +579,9 @@ extern "C" ms_status ms_k_embedding_forward(int32_t dtype, int32_t out_fp32, int
     if (d % V) return ms_fail(MS_ERR_UNSUPPORTED, "embedding: d=%d must be a multiple of %d", d, V);
     const long total = (long)n * (d / V);
     hipStream_t s = (hipStream_t)stream;
-    if (dtype == MS_F32) embedding_fwd_kernel<float, float><<<ms_cdiv(total, 256), 256, 0, s>>>(ids, (const float *)table, (float *)x, total, d);
-    else if (out_fp32) embedding_fwd_kernel<bf16_t, float><<<ms_cdiv(total, 256), 256, 0, s>>>(ids, (const bf16_t *)table, (float *)x, total, d);
-    else embedding_fwd_kernel<bf16_t, bf16_t><<<ms_cdiv(total, 256), 256, 0, s>>>(ids, (const bf16_t *)table, (bf16_t *)x, total, d);
+    if (dtype == MS_F32) embedding_fwd_kernel<float, float><<<ms_cdiv(total, 256), 256, 0, s>>>(ids, (const float *)table, (float *)x, total, d, vocab);
+    else if (out_fp32) embedding_fwd_kernel<bf16_t, float><<<ms_cdiv(total, 256), 256, 0, s>>>(ids, (const bf16_t *)table, (float *)x, total, d, vocab);
+    else embedding_fwd_kernel<bf16_t, bf16_t><<<ms_cdiv(total, 256), 256, 0, s>>>(ids, (const bf16_t *)table, (bf16_t *)x, total, d, vocab);
     MS_LAUNCH_CHECK();
     return MS_OK;
 }
@@ -583,8 +592,7 @@ extern "C" ms_status ms_k_embedding_backward(int32_t dtype, int32_t n, int32_t d
     if (!ids || !dx || !d_table || n < 0 || d <= 0 || vocab <= 0) return ms_fail(MS_ERR_INVALID_ARG, "embedding_backward: bad argument");
     const int V = dtype == MS_BF16 ? 8 : 4;
     if (d % V) return ms_fail(MS_ERR_UNSUPPORTED, "embedding: d=%d must be a multiple of %d", d, V);
-    const long total = (long)n * (d / V);
-    DISPATCH_T(dtype, { embedding_bwd_kernel<T><<<ms_cdiv(total, 256), 256, 0, (hipStream_t)stream>>>(ids, (const T *)dx, d_table, total, d); });
+    DISPATCH_T(dtype, { embedding_bwd_kernel<T><<<n, 256, 0, (hipStream_t)stream>>>(ids, (const T *)dx, d_table, d, vocab); });
     MS_LAUNCH_CHECK();
     return MS_OK;
 }
