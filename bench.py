@@ -35,6 +35,34 @@ def model_flops(work):
                 kd=2.0 * n * kd.vocab * (kd.h_teacher + kd.h_student) + 4.0 * n * kd.vocab * kd.h_student)
 
 
+def nt_gemm_shapes(work):
+    """(M, N, K, out_bytes, residual_bytes) of every A[M,K]*B[N,K]^T launch of one step (decoder sections)."""
+    n = work.n_tokens
+    out = []
+    for cfg in (work.teacher, work.student):
+        d, f = cfg.d_model, cfg.d_ffn
+        qkv = (cfg.n_q_heads + 2 * cfg.n_kv_heads) * cfg.head_dim
+        per_layer = [(n, qkv, d, 2, 0), (n, d, cfg.n_q_heads * cfg.head_dim, 4, 4), (n, 2 * f, d, 2, 0), (n, d, f, 4, 4)]
+        out += per_layer * cfg.n_layers
+    kd = work.kd
+    for v0 in range(0, kd.vocab, kd.chunk):
+        cw = min(kd.chunk, kd.vocab - v0)
+        out += [(n, cw, kd.h_teacher, 4, 0), (n, cw, kd.h_student, 4, 0)] * 2      # statistics pass + recompute
+    return out
+
+
+def measured_traffic():
+    """HBM-side bytes per NT launch from the committed counter summary (two rocprofv3 --pmc runs), or None."""
+    path = os.path.join(ROOT, "profiles", "gemm_bf16_fast_kernel_c2_hbm_traffic.txt")
+    try:
+        for line in open(path):
+            if line.startswith("gemm_nt_traffic_bytes_per_launch:"):
+                return float(line.split(":")[1])
+    except OSError:
+        pass
+    return None
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -130,6 +158,13 @@ def main():
                 unit = "TFLOP/s" if name.startswith("gemm") else "GB/s"
                 kernels[name][unit] = workv / (ms * 1e-3) / (1e12 if unit == "TFLOP/s" else 1e9)
     total_flops = fl["teacher"] + fl["student"] + fl["kd"]
+    alg_bytes = traffic = None
+    if work.teacher.arch == "decoder" and work.student.arch == "decoder":
+        shapes = nt_gemm_shapes(work)
+        if len(shapes) == g_n / prof_steps and abs(sum(2.0 * m * nn * k for m, nn, k, _, _ in shapes) * prof_steps / g_work - 1) < 1e-3:
+            alg_bytes = sum(2.0 * (m * k + nn * k) + (ob + rb) * m * nn for m, nn, k, ob, rb in shapes) / len(shapes)
+        if args.workload == "c2":
+            traffic = measured_traffic()
     result = {
         "metric": "KD step tokens/s (teacher fwd + student fwd+bwd + fused KL loss), 1 GPU",
         "value": n / sec_step, "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
@@ -144,9 +179,12 @@ def main():
         "mfma_frac_teacher_fwd": fl["teacher"] / sec_teacher / 1e12 / PEAK_BF16_TFLOPS,
         "mfma_frac_student_fwd_bwd_kd": (fl["student"] + fl["kd"]) / sec_student / 1e12 / PEAK_BF16_TFLOPS,
         "loss": loss, "logits_to_hidden_ratio": kd.vocab / kd.h_teacher,
-        "roofline": {"kernel": "gemm_bf16_kernel (A[M,K] B[N,K]^T, all forward linears and lm_head chunks)",
+        "roofline": {"kernel": "gemm_bf16_fast_kernel (A[M,K] B[N,K]^T, all forward linears and lm_head chunks)",
                      "bound": "mfma", "achieved": achieved, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
-                     "frac": achieved / PEAK_BF16_TFLOPS, "traffic": None,
+                     "frac": achieved / PEAK_BF16_TFLOPS, "traffic": traffic,
+                     "traffic_source": "profiles/gemm_bf16_fast_kernel_c2_hbm_traffic.txt (rocprofv3 --pmc FETCH_SIZE, "
+                                       "WRITE_SIZE; bytes per launch)" if traffic else None,
+                     "algorithmic_bytes_per_launch": alg_bytes,
                      "launches_per_step": g_n / prof_steps, "avg_launch_us": 1e3 * g_ms / max(g_n, 1),
                      "flops_per_launch_avg": g_work / max(g_n, 1)},
         "kernels": kernels,
