@@ -38,7 +38,16 @@ struct GemmParams {
     int k_tiles_per_split;  // in units of 64
     float alpha;
     int c_fp32, accumulate, atomic, res_fp32, vec_epilogue;
+    // KD epilogues (EPI != 0): the tile holds student logits zs; zt = teacher logits of the same chunk
+    const float *kd_zt;      // [M, kd_ldz] fp32
+    long kd_ldz;
+    float *kd_stats;         // EPI_KD_DZ: [M][8] per-token statistics (lse_t at 5, lse_s at 6), read
+    float *kd_part;          // EPI_KD_STATS: [M][kd_nparts][8] partial statistics per 64-column strip, written
+    int kd_nparts;
+    float kd_inv_t, kd_coef;
 };
+
+enum { EPI_NONE = 0, EPI_KD_DZ = 1, EPI_KD_STATS = 2 };
 
 template <int BM, int BN, bool TA, bool TB>
 __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmParams p) {
@@ -236,7 +245,7 @@ __device__ __forceinline__ void interleave_reads_with_mfma() {
     if constexpr (M > PAIRS) __builtin_amdgcn_sched_group_barrier(0x008, M - PAIRS, 0);
 }
 
-template <int BM, int BN, int WM, int WN, bool TA, bool TB>
+template <int BM, int BN, int WM, int WN, bool TA, bool TB, int EPI = EPI_NONE>
 __global__ __launch_bounds__(64 * WM * WN) void gemm_bf16_fast_kernel(GemmParams p) {
     constexpr int NT = 64 * WM * WN;
     constexpr int WTM = BM / WM, WTN = BN / WN, MI = WTM / 32, NI = WTN / 32;
@@ -369,6 +378,94 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_bf16_fast_kernel(GemmParams
     const int rsz = p.res_fp32 ? 4 : 2;
     const __amdgpu_buffer_rsrc_t rr = make_rsrc(p.residual ? p.residual : p.C, p.residual ? (long)p.M * p.ldr * rsz : 0);
     const bf16_t *bias = (const bf16_t *)p.bias;
+    if constexpr (EPI != EPI_NONE) {
+        // Same staging through LDS as the vector epilogue below (a lane ends up with 4 consecutive columns
+        // of a row), then, instead of storing the student logits zs:
+        //   EPI_KD_DZ:    dz = coef * (exp(zs/T - lse_s) - exp(zt/T - lse_t)) -> C (storage dtype)
+        //   EPI_KD_STATS: per row, over this wave's 64 columns: max and sum of exponentials of zt/T and
+        //                 zs/T and the cross term sum e^{zt/T - m_t} (zt - zs)/T -> kd_part
+        static_assert(WTN == 64 && !TA && !TB, "KD epilogues are built for the K-contiguous layout");
+        constexpr int WPA = BM / 64;
+        float *stg = (float *)((wave / WPA) ? As1 : As0) + (wave % WPA) * 2048;
+        const int prow = lane >> 4, pcol = (lane & 15) * 4;
+        const int colg = n0 + wn * WTN + pcol;
+        const bool cok = colg < p.N;
+        const __amdgpu_buffer_rsrc_t rz = make_rsrc(p.kd_zt, (long)p.M * p.kd_ldz * 4);
+        const float it = p.kd_inv_t;
+#pragma unroll
+        for (int i = 0; i < MI; ++i) {
+#pragma unroll
+            for (int j = 0; j < NI; ++j)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    const int row = 8 * (r >> 2) + 4 * fhalf + (r & 3);
+                    stg[row * 64 + ((j * 32 + frow) ^ (fhalf << 5))] = acc[i][j][r] * p.alpha;
+                }
+#pragma unroll
+            for (int ps = 0; ps < 8; ++ps) {
+                const int row = ps * 4 + prow;
+                const float4 t = *(const float4 *)(stg + row * 64 + (pcol ^ (((row >> 2) & 1) << 5)));
+                const float zs[4] = {t.x, t.y, t.z, t.w};
+                const long rowg = m0 + wm * WTM + i * 32 + row;
+                const bool rok = rowg < p.M;
+                const u32x4 q = __builtin_amdgcn_raw_buffer_load_b128(rz, cok ? (unsigned)((rowg * p.kd_ldz + colg) * 4) : kOob, 0, 0);
+                float zt[4];
+#pragma unroll
+                for (int e = 0; e < 4; ++e) zt[e] = __uint_as_float(q[e]);
+                if constexpr (EPI == EPI_KD_DZ) {
+                    const float lse_t = rok ? p.kd_stats[rowg * 8 + 5] : 0.f, lse_s = rok ? p.kd_stats[rowg * 8 + 6] : 0.f;
+                    float v[4];
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) v[e] = p.kd_coef * (__expf(zs[e] * it - lse_s) - __expf(zt[e] * it - lse_t));
+                    const unsigned co = cok ? (unsigned)((rowg * p.ldc + colg) * esz) : kOob;
+                    if (p.c_fp32) {
+                        u32x4 w;
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) w[e] = __builtin_bit_cast(unsigned, v[e]);
+                        __builtin_amdgcn_raw_buffer_store_b128(w, rc, co, 0, 0);
+                    } else {
+                        u32x2 w;
+                        w[0] = (unsigned)__builtin_bit_cast(unsigned short, (bf16_t)v[0]) | ((unsigned)__builtin_bit_cast(unsigned short, (bf16_t)v[1]) << 16);
+                        w[1] = (unsigned)__builtin_bit_cast(unsigned short, (bf16_t)v[2]) | ((unsigned)__builtin_bit_cast(unsigned short, (bf16_t)v[3]) << 16);
+                        __builtin_amdgcn_raw_buffer_store_b64(w, rc, co, 0, 0);
+                    }
+                } else {
+                    // the 16 lanes that share a row reduce with xor-shuffles inside their group
+                    float mt = cok ? fmaxf(fmaxf(zt[0], zt[1]), fmaxf(zt[2], zt[3])) : -INFINITY;
+                    float ms = cok ? fmaxf(fmaxf(zs[0], zs[1]), fmaxf(zs[2], zs[3])) : -INFINITY;
+#pragma unroll
+                    for (int o = 1; o < 16; o <<= 1) {
+                        mt = fmaxf(mt, __shfl_xor(mt, o, 64));
+                        ms = fmaxf(ms, __shfl_xor(ms, o, 64));
+                    }
+                    mt *= it; ms *= it;                                   // T > 0
+                    const float mtu = mt == -INFINITY ? 0.f : mt, msu = ms == -INFINITY ? 0.f : ms;
+                    float st = 0.f, ss = 0.f, ac = 0.f;
+                    if (cok) {
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) {
+                            const float et = __expf(zt[e] * it - mtu);
+                            st += et;
+                            ac += et * (zt[e] - zs[e]) * it;
+                            ss += __expf(zs[e] * it - msu);
+                        }
+                    }
+#pragma unroll
+                    for (int o = 1; o < 16; o <<= 1) {
+                        st += __shfl_xor(st, o, 64);
+                        ss += __shfl_xor(ss, o, 64);
+                        ac += __shfl_xor(ac, o, 64);
+                    }
+                    if ((lane & 15) == 0 && rok && n0 + wn * WTN < p.N) {
+                        float *o = p.kd_part + ((long)rowg * p.kd_nparts + (n0 + wn * WTN) / 64) * 8;
+                        *(float4 *)o = make_float4(mt, st, ms, ss);
+                        o[4] = ac;
+                    }
+                }
+            }
+        }
+        return;
+    }
     if (p.vec_epilogue) {
         // Each wave passes its accumulators through LDS, 32 rows at a time, to turn the MFMA layout
         // (a lane owns one column) into rows: a lane then handles 4 consecutive columns of a row, so
@@ -531,6 +628,10 @@ __global__ __launch_bounds__(256) void gemm_f32_kernel(GemmF32Params p) {
 MS_INST(256, 4, false, false); MS_INST(256, 4, false, true); MS_INST(256, 4, true, false); MS_INST(256, 4, true, true);
 MS_INST(128, 2, false, false); MS_INST(128, 2, false, true); MS_INST(128, 2, true, false); MS_INST(128, 2, true, true);
 #undef MS_INST
+template __global__ void gemm_bf16_fast_kernel<256, 256, 2, 4, false, false, EPI_KD_DZ>(GemmParams);
+template __global__ void gemm_bf16_fast_kernel<256, 256, 2, 4, false, false, EPI_KD_STATS>(GemmParams);
+template __global__ void gemm_bf16_fast_kernel<128, 128, 2, 2, false, false, EPI_KD_DZ>(GemmParams);
+template __global__ void gemm_bf16_fast_kernel<128, 128, 2, 2, false, false, EPI_KD_STATS>(GemmParams);
 
 template <int BM, int BN, int WM, int WN>
 ms_status launch_bf16_fast(const GemmParams &p, int ta, int tb, int splits, hipStream_t s) {
@@ -637,4 +738,50 @@ extern "C" ms_status ms_k_gemm(int32_t dtype, int32_t trans_a, int32_t trans_b, 
     if (big) return launch_bf16_fast<256, 256, 2, 4>(p, trans_a, trans_b, splits, s);
     if (fast) return launch_bf16_fast<128, 128, 2, 2>(p, trans_a, trans_b, splits, s);
     return launch_bf16<128, 128>(p, trans_a, trans_b, splits, s);
+}
+
+// ------------------------------------------------------------------ student-logits GEMM with KD epilogues
+// zs = A[M,K] B[N,K]^T is never stored: mode EPI_KD_STATS folds it (with the teacher logits zt of the same
+// chunk) into per-strip partial statistics, mode EPI_KD_DZ turns it into dz.  bf16 fast path only.
+bool gemm_kd_epilogue_supported(int M, int N, int K, const void *A, long lda, const void *B, long ldb, const float *zt,
+                                long ldz, const void *dz, long lddz, int dz_fp32) {
+    auto al = [](const void *q) { return ((uintptr_t)q & 15) == 0; };
+    const long lim = (1L << 32) - (1L << 20);
+    static const int forced = [] { const char *e = getenv("MS_GEMM_TILE"); return e ? atoi(e) : 0; }();
+    return forced >= 0 && M > 0 && N > 0 && K > 0 && K % BK == 0 && N % 4 == 0 && al(A) && al(B) && al(zt) && lda % 8 == 0 &&
+           ldb % 8 == 0 && ldz % 4 == 0 && ((long)M + 256) * lda * 2 < lim && ((long)N + 256) * ldb * 2 < lim &&
+           ((long)M + 256) * ldz * 4 < lim && (!dz || (al(dz) && lddz % 4 == 0 && ((long)M + 256) * lddz * (dz_fp32 ? 4 : 2) < lim));
+}
+
+ms_status gemm_kd_epilogue(int mode, int M, int N, int K, const void *A, long lda, const void *B, long ldb, const float *zt,
+                           long ldz, float *stats, float *part, int nparts, float inv_t, float coef, void *dz, long lddz,
+                           int dz_fp32, hipStream_t s) {
+    if (!gemm_kd_epilogue_supported(M, N, K, A, lda, B, ldb, zt, ldz, mode == EPI_KD_DZ ? dz : nullptr, lddz, dz_fp32))
+        return ms_fail(MS_ERR_UNSUPPORTED, "gemm_kd_epilogue: shape or alignment outside the fast path");
+    if ((mode == EPI_KD_DZ && (!dz || !stats)) || (mode == EPI_KD_STATS && (!part || nparts < ms_cdiv(N, 64))) ||
+        (mode != EPI_KD_DZ && mode != EPI_KD_STATS))
+        return ms_fail(MS_ERR_INVALID_ARG, "gemm_kd_epilogue: bad mode or null buffer");
+    GemmParams p = {};
+    p.A = A; p.B = B; p.C = dz; p.lda = lda; p.ldb = ldb; p.ldc = lddz; p.M = M; p.N = N; p.K = K; p.alpha = 1.f;
+    p.c_fp32 = dz_fp32;
+    p.kd_zt = zt; p.kd_ldz = ldz; p.kd_stats = stats; p.kd_part = part; p.kd_nparts = nparts; p.kd_inv_t = inv_t; p.kd_coef = coef;
+    static const int forced = [] { const char *e = getenv("MS_GEMM_TILE"); return e ? atoi(e) : 0; }();
+    const long tiles256 = (long)ms_cdiv(M, 256) * ms_cdiv(N, 256), tiles128 = (long)ms_cdiv(M, 128) * ms_cdiv(N, 128);
+    const double eff256 = (double)tiles256 / (double)(ms_cdiv(tiles256, 256) * 256L);
+    const double eff128 = (double)tiles128 / (double)(ms_cdiv(tiles128, 512) * 512L);
+    const bool big = forced > 0 ? forced == 256 : (tiles256 >= 192 && 1.25 * eff256 > eff128);
+    const int BM = big ? 256 : 128;
+    p.tiles_m = ms_cdiv(M, BM); p.tiles_n = ms_cdiv(N, BM);
+    p.k_tiles_per_split = ms_cdiv(K, BK);
+    dim3 grid(p.tiles_m * p.tiles_n, 1);
+    ProfScope ps(0, 2.0 * M * N * K, s);
+    if (big) {
+        if (mode == EPI_KD_DZ) gemm_bf16_fast_kernel<256, 256, 2, 4, false, false, EPI_KD_DZ><<<grid, 512, 0, s>>>(p);
+        else gemm_bf16_fast_kernel<256, 256, 2, 4, false, false, EPI_KD_STATS><<<grid, 512, 0, s>>>(p);
+    } else {
+        if (mode == EPI_KD_DZ) gemm_bf16_fast_kernel<128, 128, 2, 2, false, false, EPI_KD_DZ><<<grid, 256, 0, s>>>(p);
+        else gemm_bf16_fast_kernel<128, 128, 2, 2, false, false, EPI_KD_STATS><<<grid, 256, 0, s>>>(p);
+    }
+    MS_LAUNCH_CHECK();
+    return MS_OK;
 }

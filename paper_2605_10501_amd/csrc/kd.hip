@@ -6,6 +6,9 @@
 // term sum_v e^{zt/T - m_t} (zt - zs)/T.  From those, KL_tok = A/s_t - lse_t + lse_s.
 // Pass 2 recomputes each chunk's logits, forms dz = (scale/T)(q - p) in the storage dtype and
 // feeds it to the two gradient GEMMs (dHs accumulated in fp32 over chunks, dWs chunk rows +=).
+// On the bf16 fast path the student logits are never stored: the epilogue of their GEMM reads the
+// teacher logits of the same tile and emits per-strip partial statistics (pass 1, merged per token
+// by a small kernel) or dz itself (pass 2).
 #include "common.h"
 #include "launch.h"
 
@@ -117,6 +120,45 @@ __global__ __launch_bounds__(256) void kd_dz_kernel(const float *__restrict__ zt
         o[e] = from_f32<T>(coef * (__expf(bv[e] * inv_t - lse_s) - __expf(av[e] * inv_t - lse_t)));
 }
 
+// Fused path: merges the per-strip partial statistics that the student-logits GEMM epilogue wrote for one
+// chunk ([n][nparts][8]: m_t, s_t, m_s, s_s, A) into the running per-token statistics.  One wave per token.
+__global__ __launch_bounds__(256) void kd_combine_kernel(const float *__restrict__ part, int nparts, int n, int first,
+                                                          float *__restrict__ stats) {
+    const int lane = threadIdx.x & 63;
+    const long t = (long)blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (t >= n) return;
+    float m_t = -INFINITY, s_t = 0.f, m_s = -INFINITY, s_s = 0.f, a = 0.f;
+    auto merge = [&](float mt_i, float st_i, float ms_i, float ss_i, float a_i) {
+        const float nt = fmaxf(m_t, mt_i), ns = fmaxf(m_s, ms_i);
+        const float ut = nt == -INFINITY ? 0.f : nt, us = ns == -INFINITY ? 0.f : ns;
+        const float ft0 = __expf(m_t - ut), ft1 = __expf(mt_i - ut), fs0 = __expf(m_s - us), fs1 = __expf(ms_i - us);
+        s_t = s_t * ft0 + st_i * ft1;
+        a = a * ft0 + a_i * ft1;
+        s_s = s_s * fs0 + ss_i * fs1;
+        m_t = nt;
+        m_s = ns;
+    };
+    for (int i = lane; i < nparts; i += 64) {
+        const float *q = part + (t * nparts + i) * 8;
+        const float4 v = *(const float4 *)q;
+        merge(v.x, v.y, v.z, v.w, q[4]);
+    }
+    // across the wave: common maxima, rescaled sums
+    const float wt = wave_max(m_t), wsm = wave_max(m_s);
+    const float ut = wt == -INFINITY ? 0.f : wt, us = wsm == -INFINITY ? 0.f : wsm;
+    const float ft = __expf(m_t - ut), fs = __expf(m_s - us);
+    s_t = wave_sum(s_t * ft);
+    a = wave_sum(a * ft);
+    s_s = wave_sum(s_s * fs);
+    m_t = wt;
+    m_s = wsm;
+    if (lane == 0) {
+        float *st = stats + t * kStat;
+        if (!first) merge(st[0], st[1], st[2], st[3], st[4]);
+        st[0] = m_t; st[1] = s_t; st[2] = m_s; st[3] = s_s; st[4] = a;
+    }
+}
+
 struct KdPlan {
     float *zt, *zs, *stats, *dhs;
     void *dz;
@@ -171,25 +213,46 @@ ms_status kd_forward_backward(const ms_kd_config *kd, int n, const void *h_t, co
     const char *wt = (const char *)kd->w_teacher_dev, *wsd = (const char *)kd->w_student_dev;
     const int passes = (d_h_s || d_w_s) ? 2 : 1;
     if (d_h_s) MS_TRY(launch_fill_f32(p.dhs, (long)n * Hs, 0.f, s));
+    // bf16 fast path: the student-logits GEMM consumes its own output (statistics in pass 1, dz in pass 2)
+    // together with the stored teacher logits; the zs buffer then only holds the per-strip partials
+    bool fused = dt == MS_BF16;
+    for (int v0 = 0; v0 < V && fused; v0 += Cv) {
+        const int cw = V - v0 < Cv ? V - v0 : Cv;
+        fused = gemm_kd_epilogue_supported(n, cw, Hs, h_s, Hs, wsd + (size_t)v0 * Hs * es, Hs, p.zt, Cv, p.dz, Cv, 0);
+    }
     for (int pass = 0; pass < passes; ++pass) {
         for (int v0 = 0; v0 < V; v0 += Cv) {
             const int cw = V - v0 < Cv ? V - v0 : Cv;
             MS_TRY(ms_k_gemm(dt, 0, 0, n, cw, Ht, 1.f, h_t, Ht, wt + (size_t)v0 * Ht * es, Ht, p.zt, Cv, 1, 0, nullptr, nullptr, 0, 0, 1, s));
-            MS_TRY(ms_k_gemm(dt, 0, 0, n, cw, Hs, 1.f, h_s, Hs, wsd + (size_t)v0 * Hs * es, Hs, p.zs, Cv, 1, 0, nullptr, nullptr, 0, 0, 1, s));
-            if (pass == 0) {
-                ProfScope ps(9, 8.0 * n * cw, s);
-                kd_stats_kernel<<<n, 256, 0, s>>>(p.zt, p.zs, Cv, cw, inv_t, v0 == 0, p.stats);
+            if (fused) {
+                const int nparts = ms_cdiv(cw, 64);
+                if (pass == 0) {
+                    MS_TRY(gemm_kd_epilogue(2, n, cw, Hs, h_s, Hs, wsd + (size_t)v0 * Hs * es, Hs, p.zt, Cv, nullptr, p.zs, nparts,
+                                            inv_t, 0.f, nullptr, 0, 0, s));
+                    ProfScope ps(9, 32.0 * n * nparts, s);
+                    kd_combine_kernel<<<ms_cdiv(n, 4), 256, 0, s>>>(p.zs, nparts, n, v0 == 0, p.stats);
+                    MS_LAUNCH_CHECK();
+                    continue;
+                }
+                MS_TRY(gemm_kd_epilogue(1, n, cw, Hs, h_s, Hs, wsd + (size_t)v0 * Hs * es, Hs, p.zt, Cv, p.stats, nullptr, 0, inv_t,
+                                        kd->loss_scale * inv_t, p.dz, Cv, 0, s));
+            } else {
+                MS_TRY(ms_k_gemm(dt, 0, 0, n, cw, Hs, 1.f, h_s, Hs, wsd + (size_t)v0 * Hs * es, Hs, p.zs, Cv, 1, 0, nullptr, nullptr, 0, 0, 1, s));
+                if (pass == 0) {
+                    ProfScope ps(9, 8.0 * n * cw, s);
+                    kd_stats_kernel<<<n, 256, 0, s>>>(p.zt, p.zs, Cv, cw, inv_t, v0 == 0, p.stats);
+                    MS_LAUNCH_CHECK();
+                    continue;
+                }
+                const float coef = kd->loss_scale * inv_t;
+                dim3 grid(ms_cdiv(cw, 1024), n);
+                {
+                    ProfScope ps(10, (8.0 + es) * n * cw, s);
+                    if (dt == MS_BF16) kd_dz_kernel<bf16_t><<<grid, 256, 0, s>>>(p.zt, p.zs, Cv, cw, inv_t, coef, p.stats, (bf16_t *)p.dz);
+                    else kd_dz_kernel<float><<<grid, 256, 0, s>>>(p.zt, p.zs, Cv, cw, inv_t, coef, p.stats, (float *)p.dz);
+                }
                 MS_LAUNCH_CHECK();
-                continue;
             }
-            const float coef = kd->loss_scale * inv_t;
-            dim3 grid(ms_cdiv(cw, 1024), n);
-            {
-                ProfScope ps(10, (8.0 + es) * n * cw, s);
-                if (dt == MS_BF16) kd_dz_kernel<bf16_t><<<grid, 256, 0, s>>>(p.zt, p.zs, Cv, cw, inv_t, coef, p.stats, (bf16_t *)p.dz);
-                else kd_dz_kernel<float><<<grid, 256, 0, s>>>(p.zt, p.zs, Cv, cw, inv_t, coef, p.stats, (float *)p.dz);
-            }
-            MS_LAUNCH_CHECK();
             if (d_h_s)  // dHs[N, Hs] += dz[N, cw] Ws_c[cw, Hs]
                 MS_TRY(ms_k_gemm(dt, 0, 1, n, Hs, cw, 1.f, p.dz, Cv, wsd + (size_t)v0 * Hs * es, Hs, p.dhs, Hs, 1, 1, nullptr, nullptr, 0, 0, 1, s));
             if (d_w_s)  // dWs_c[cw, Hs] += dz^T[cw, N] Hs[N, Hs]

@@ -6,6 +6,14 @@ ms_status launch_fill_f32(float *p, long n, float v, hipStream_t s);
 ms_status launch_convert_from_f32(int dtype, const float *src, void *dst, long n, hipStream_t s);
 ms_status launch_convert_bf16_to_f32(const void *src, float *dst, long n, hipStream_t s);
 
+// Student-logits GEMM whose epilogue consumes the logits instead of storing them (gemm.hip); mode 1: dz, mode 2:
+// per-strip partial statistics [M][nparts][8] = (m_t, s_t, m_s, s_s, A, -, -, -) over 64-column strips.
+bool gemm_kd_epilogue_supported(int M, int N, int K, const void *A, long lda, const void *B, long ldb, const float *zt,
+                                long ldz, const void *dz, long lddz, int dz_fp32);
+ms_status gemm_kd_epilogue(int mode, int M, int N, int K, const void *A, long lda, const void *B, long ldb, const float *zt,
+                           long ldz, float *stats, float *part, int nparts, float inv_t, float coef, void *dz, long lddz,
+                           int dz_fp32, hipStream_t s);
+
 // KD-loss pieces (kd.hip)
 ms_status kd_forward_backward(const ms_kd_config *kd, int n_tokens, const void *h_teacher, const void *h_student,
                               float *loss_dev, float *kl_tok_dev, void *d_h_student, void *d_w_student,
