@@ -45,9 +45,14 @@ struct GemmParams {
     float *kd_part;          // EPI_KD_STATS: [M][kd_nparts][8] partial statistics per 64-column strip, written
     int kd_nparts;
     float kd_inv_t, kd_coef;
+    // EPI_SWIGLU: B = [gate rows (sg_f) | up rows (sg_f)], N = sg_f output columns; C = silu(gate) * up
+    // [M, ldc]; sg_gu (optional) also receives the rounded gate | up pre-activations [M, sg_ldgu]
+    int sg_f;
+    void *sg_gu;
+    long sg_ldgu;
 };
 
-enum { EPI_NONE = 0, EPI_KD_DZ = 1, EPI_KD_STATS = 2 };
+enum { EPI_NONE = 0, EPI_KD_DZ = 1, EPI_KD_STATS = 2, EPI_SWIGLU = 3 };
 
 template <int BM, int BN, bool TA, bool TB>
 __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmParams p) {
@@ -202,6 +207,33 @@ struct RowTileStager {
     }
 };
 
+// B tile of the fused gate/up + SwiGLU GEMM: tile row R = 64 * w + 32 * u + l holds weight row
+// u * F + col0 + 32 * w + l (u = 0 gate, 1 up), so that the two 32-column blocks of wave column w are
+// the gate and the up pre-activation of the same 32 output columns (same lane, same register).
+template <int ROWS, int NWAVES>
+struct GateUpStager {
+    static constexpr int NI = ROWS / 8 / NWAVES;
+    unsigned lanepart;                     // (lane >> 3) rows + swizzle-free part, in bytes
+    unsigned ldb;                          // bytes per row
+    int x, col0, f;
+    __device__ __forceinline__ void init(long ld, int col0_, int f_, int lane) {
+        ldb = (unsigned)(ld * 2);
+        lanepart = (unsigned)(lane >> 3) * ldb;
+        x = (lane & 7) ^ (lane >> 3);
+        col0 = col0_;
+        f = f_;
+    }
+    __device__ __forceinline__ void issue(__amdgpu_buffer_rsrc_t rs, bf16_t *tile, int k0, int wave, unsigned inv) const {
+#pragma unroll
+        for (int i = 0; i < NI; ++i) {
+            const int g = wave * NI + i;                                   // 8-row group of the tile (scalar)
+            const int wrow = ((g >> 2) & 1) * f + col0 + (g >> 3) * 32 + (g & 3) * 8;
+            const unsigned voff = ((unsigned)wrow * ldb + lanepart + ((x ^ (g & 3)) << 4)) | inv;
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(rs, (lds_void *)(tile + g * 8 * BK), 16, voff, k0 * 2, 0, 0);
+        }
+    }
+};
+
 template <int ROWS, int NWAVES>
 struct DmaStager {
     static constexpr int NI = ROWS / 8 / NWAVES;   // instructions per wave per tile
@@ -280,12 +312,16 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_bf16_fast_kernel(GemmParams
 
     const bf16_t *A = (const bf16_t *)p.A, *B = (const bf16_t *)p.B;
     std::conditional_t<TA, RowTileStager<BM, WM * WN>, DmaStager<BM, WM * WN>> da;
-    std::conditional_t<TB, RowTileStager<BN, WM * WN>, DmaStager<BN, WM * WN>> db;
+    std::conditional_t<EPI == EPI_SWIGLU, GateUpStager<BN, WM * WN>,
+                       std::conditional_t<TB, RowTileStager<BN, WM * WN>, DmaStager<BN, WM * WN>>> db;
     // descriptor ranges: rows x leading dimension of the matrix as stored ([M or N][K], or [K][M or N])
     const __amdgpu_buffer_rsrc_t ra = make_rsrc(A, TA ? ((long)(p.K - 1) * p.lda + p.M) * 2 : ((long)(p.M - 1) * p.lda + p.K) * 2);
-    const __amdgpu_buffer_rsrc_t rb = make_rsrc(B, TB ? ((long)(p.K - 1) * p.ldb + p.N) * 2 : ((long)(p.N - 1) * p.ldb + p.K) * 2);
+    const __amdgpu_buffer_rsrc_t rb = make_rsrc(B, TB ? ((long)(p.K - 1) * p.ldb + p.N) * 2
+                                                      : ((long)((EPI == EPI_SWIGLU ? 2 * p.sg_f : p.N) - 1) * p.ldb + p.K) * 2);
     if constexpr (TA) da.init(p.lda, m0, wave, lane); else da.init(p.lda, m0, lane);
-    if constexpr (TB) db.init(p.ldb, n0, wave, lane); else db.init(p.ldb, n0, lane);
+    if constexpr (EPI == EPI_SWIGLU) db.init(p.ldb, n0 / 2, p.sg_f, lane);   // tile tn covers output columns tn * BN/2 ..
+    else if constexpr (TB) db.init(p.ldb, n0, wave, lane);
+    else db.init(p.ldb, n0, lane);
 
     f32x16 acc[MI][NI];
 #pragma unroll
@@ -378,7 +414,54 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_bf16_fast_kernel(GemmParams
     const int rsz = p.res_fp32 ? 4 : 2;
     const __amdgpu_buffer_rsrc_t rr = make_rsrc(p.residual ? p.residual : p.C, p.residual ? (long)p.M * p.ldr * rsz : 0);
     const bf16_t *bias = (const bf16_t *)p.bias;
-    if constexpr (EPI != EPI_NONE) {
+    if constexpr (EPI == EPI_SWIGLU) {
+        // acc[i][0] = gate, acc[i][1] = up of output columns n0/2 + wn*32 + (0..31).  Both are rounded to
+        // the storage type first (they are the values a separate activation kernel would read back), staged
+        // through LDS as [32 rows][gate 32 | up 32], and each lane then owns 4 consecutive output columns.
+        static_assert(WTN == 64 && NI == 2 && !TA && !TB, "SwiGLU epilogue is built for the K-contiguous layout");
+        constexpr int WPA = BM / 64;
+        float *stg = (float *)((wave / WPA) ? As1 : As0) + (wave % WPA) * 2048;
+        const int prow = lane >> 3, pcol = (lane & 7) * 4;
+        const int colg = n0 / 2 + wn * 32 + pcol;
+        const bool cok = colg < p.N;
+        const __amdgpu_buffer_rsrc_t rg = make_rsrc(p.sg_gu ? p.sg_gu : p.C, p.sg_gu ? (long)p.M * p.sg_ldgu * 2 : 0);
+        auto pack4 = [](const float *v) {
+            u32x2 w;
+            w[0] = (unsigned)__builtin_bit_cast(unsigned short, (bf16_t)v[0]) | ((unsigned)__builtin_bit_cast(unsigned short, (bf16_t)v[1]) << 16);
+            w[1] = (unsigned)__builtin_bit_cast(unsigned short, (bf16_t)v[2]) | ((unsigned)__builtin_bit_cast(unsigned short, (bf16_t)v[3]) << 16);
+            return w;
+        };
+#pragma unroll
+        for (int i = 0; i < MI; ++i) {
+#pragma unroll
+            for (int j = 0; j < NI; ++j)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    const int row = 8 * (r >> 2) + 4 * fhalf + (r & 3);
+                    stg[row * 64 + ((j * 32 + frow) ^ (fhalf << 5))] = (float)(bf16_t)(acc[i][j][r] * p.alpha);
+                }
+#pragma unroll
+            for (int ps = 0; ps < 4; ++ps) {
+                const int row = ps * 8 + prow;
+                const int flip = ((row >> 2) & 1) << 5;
+                const float4 g4 = *(const float4 *)(stg + row * 64 + (pcol ^ flip));
+                const float4 u4 = *(const float4 *)(stg + row * 64 + ((32 + pcol) ^ flip));
+                const float gv[4] = {g4.x, g4.y, g4.z, g4.w}, uv[4] = {u4.x, u4.y, u4.z, u4.w};
+                float a[4];
+#pragma unroll
+                for (int e = 0; e < 4; ++e) a[e] = gv[e] / (1.f + __expf(-gv[e])) * uv[e];
+                const long rowg = m0 + wm * WTM + i * 32 + row;
+                __builtin_amdgcn_raw_buffer_store_b64(pack4(a), rc, cok ? (unsigned)((rowg * p.ldc + colg) * 2) : kOob, 0, 0);
+                if (p.sg_gu) {
+                    const unsigned go = cok ? (unsigned)((rowg * p.sg_ldgu + colg) * 2) : kOob;
+                    __builtin_amdgcn_raw_buffer_store_b64(pack4(gv), rg, go, 0, 0);
+                    __builtin_amdgcn_raw_buffer_store_b64(pack4(uv), rg, cok ? go + (unsigned)p.sg_f * 2 : kOob, 0, 0);
+                }
+            }
+        }
+        return;
+    }
+    if constexpr (EPI == EPI_KD_DZ || EPI == EPI_KD_STATS) {
         // Same staging through LDS as the vector epilogue below (a lane ends up with 4 consecutive columns
         // of a row), then, instead of storing the student logits zs:
         //   EPI_KD_DZ:    dz = coef * (exp(zs/T - lse_s) - exp(zt/T - lse_t)) -> C (storage dtype)
@@ -632,6 +715,8 @@ template __global__ void gemm_bf16_fast_kernel<256, 256, 2, 4, false, false, EPI
 template __global__ void gemm_bf16_fast_kernel<256, 256, 2, 4, false, false, EPI_KD_STATS>(GemmParams);
 template __global__ void gemm_bf16_fast_kernel<128, 128, 2, 2, false, false, EPI_KD_DZ>(GemmParams);
 template __global__ void gemm_bf16_fast_kernel<128, 128, 2, 2, false, false, EPI_KD_STATS>(GemmParams);
+template __global__ void gemm_bf16_fast_kernel<256, 256, 2, 4, false, false, EPI_SWIGLU>(GemmParams);
+template __global__ void gemm_bf16_fast_kernel<128, 128, 2, 2, false, false, EPI_SWIGLU>(GemmParams);
 
 template <int BM, int BN, int WM, int WN>
 ms_status launch_bf16_fast(const GemmParams &p, int ta, int tb, int splits, hipStream_t s) {
@@ -782,6 +867,43 @@ ms_status gemm_kd_epilogue(int mode, int M, int N, int K, const void *A, long ld
         if (mode == EPI_KD_DZ) gemm_bf16_fast_kernel<128, 128, 2, 2, false, false, EPI_KD_DZ><<<grid, 256, 0, s>>>(p);
         else gemm_bf16_fast_kernel<128, 128, 2, 2, false, false, EPI_KD_STATS><<<grid, 256, 0, s>>>(p);
     }
+    MS_LAUNCH_CHECK();
+    return MS_OK;
+}
+
+// ------------------------------------------------------------------ fused gate/up GEMM + SwiGLU
+// act[M, F] = silu(A W_gate^T) * (A W_up^T) with W = [gate rows | up rows] ([2F, K]); gate_up (optional,
+// [M, 2F]) also receives the rounded pre-activations for the backward pass.  bf16 fast path only.
+bool gemm_swiglu_supported(int M, int F, int K, const void *A, long lda, const void *W, long ldw, const void *act, long ldact,
+                           const void *gate_up, long ldgu) {
+    auto al = [](const void *q) { return ((uintptr_t)q & 15) == 0; };
+    const long lim = (1L << 32) - (1L << 20);
+    static const int forced = [] { const char *e = getenv("MS_GEMM_TILE"); return e ? atoi(e) : 0; }();
+    return forced >= 0 && M > 0 && F > 0 && K > 0 && K % BK == 0 && F % 4 == 0 && al(A) && al(W) && al(act) && lda % 8 == 0 &&
+           ldw % 8 == 0 && ldact % 4 == 0 && ((long)M + 256) * lda * 2 < lim && (2L * F + 256) * ldw * 2 < lim &&
+           ((long)M + 256) * ldact * 2 < lim && (!gate_up || (al(gate_up) && ldgu % 4 == 0 && ((long)M + 256) * ldgu * 2 < lim));
+}
+
+ms_status gemm_swiglu(int M, int F, int K, const void *A, long lda, const void *W, long ldw, void *act, long ldact,
+                      void *gate_up, long ldgu, hipStream_t s) {
+    if (!gemm_swiglu_supported(M, F, K, A, lda, W, ldw, act, ldact, gate_up, ldgu))
+        return ms_fail(MS_ERR_UNSUPPORTED, "gemm_swiglu: shape or alignment outside the fast path");
+    GemmParams p = {};
+    p.A = A; p.B = W; p.C = act; p.lda = lda; p.ldb = ldw; p.ldc = ldact; p.M = M; p.N = F; p.K = K; p.alpha = 1.f;
+    p.sg_f = F; p.sg_gu = gate_up; p.sg_ldgu = ldgu;
+    static const int forced = [] { const char *e = getenv("MS_GEMM_TILE"); return e ? atoi(e) : 0; }();
+    // a tile covers BN/2 output columns (BN weight rows: gate and up)
+    const long tiles256 = (long)ms_cdiv(M, 256) * ms_cdiv(F, 128), tiles128 = (long)ms_cdiv(M, 128) * ms_cdiv(F, 64);
+    const double eff256 = (double)tiles256 / (double)(ms_cdiv(tiles256, 256) * 256L);
+    const double eff128 = (double)tiles128 / (double)(ms_cdiv(tiles128, 512) * 512L);
+    const bool big = forced > 0 ? forced == 256 : (tiles256 >= 192 && 1.25 * eff256 > eff128);
+    const int BM = big ? 256 : 128;
+    p.tiles_m = ms_cdiv(M, BM); p.tiles_n = ms_cdiv(F, BM / 2);
+    p.k_tiles_per_split = ms_cdiv(K, BK);
+    dim3 grid(p.tiles_m * p.tiles_n, 1);
+    ProfScope ps(0, 4.0 * M * F * K, s);
+    if (big) gemm_bf16_fast_kernel<256, 256, 2, 4, false, false, EPI_SWIGLU><<<grid, 512, 0, s>>>(p);
+    else gemm_bf16_fast_kernel<128, 128, 2, 2, false, false, EPI_SWIGLU><<<grid, 256, 0, s>>>(p);
     MS_LAUNCH_CHECK();
     return MS_OK;
 }

@@ -14,6 +14,13 @@ ms_status gemm_kd_epilogue(int mode, int M, int N, int K, const void *A, long ld
                            long ldz, float *stats, float *part, int nparts, float inv_t, float coef, void *dz, long lddz,
                            int dz_fp32, hipStream_t s);
 
+// Fused gate/up GEMM + SwiGLU (gemm.hip): act[M,F] = silu(A Wg^T) * (A Wu^T), W = [Wg | Wu] rows; gate_up (may be
+// null) receives the rounded pre-activations [M, 2F].
+bool gemm_swiglu_supported(int M, int F, int K, const void *A, long lda, const void *W, long ldw, const void *act, long ldact,
+                           const void *gate_up, long ldgu);
+ms_status gemm_swiglu(int M, int F, int K, const void *A, long lda, const void *W, long ldw, void *act, long ldact,
+                      void *gate_up, long ldgu, hipStream_t s);
+
 // KD-loss pieces (kd.hip)
 ms_status kd_forward_backward(const ms_kd_config *kd, int n_tokens, const void *h_teacher, const void *h_student,
                               float *loss_dev, float *kl_tok_dev, void *d_h_student, void *d_w_student,

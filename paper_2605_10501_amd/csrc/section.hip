@@ -30,6 +30,7 @@ struct Plan {
     void *dy0, *dy1, *dx2, *dh, *d_o, *dqkv, *da, *dup, *dhs;
     void *norm_scratch, *attn_scratch;
     size_t bytes;
+    bool bwd;                      // layers keep their activations for a backward pass
 };
 
 struct Dims {
@@ -60,6 +61,7 @@ Plan make_plan(const ms_section_config *c, int n, int max_seqlen, bool bwd, void
     auto res = [&](size_t cols) { return a.take<void>(N * cols * 4); };   // residual stream: fp32
     auto f32 = [&](size_t cnt) { return a.take<float>(cnt * 4); };
     const int nbuf = bwd ? c->n_layers : 1;
+    p.bwd = bwd;
     p.layers.resize(nbuf);
     for (auto &l : p.layers) {
         l.x = bwd ? res(m.d) : nullptr;
@@ -177,8 +179,15 @@ struct Exec {
                                       l.qkv, l.o, l.lse, s));
         MS_TRY(linear(l.o, m.dattn, w.w_o, m.dec ? nullptr : w.b_o, m.d, l.x2, x));
         MS_TRY(ms_k_norm_forward(kind, dt, 1, m.n, m.d, c->norm_eps, l.x2, w.norm2_g, w.norm2_b, l.h2, l.mean2, l.rstd2, s));
-        MS_TRY(linear(l.h2, m.d, w.w_up, m.dec ? nullptr : w.b_up, m.dup, l.up, nullptr));
-        MS_TRY(ms_k_act_forward(m.dec ? 0 : 1, dt, m.n, m.f, l.up, l.act, s));
+        // decoder, bf16: SwiGLU runs in the epilogue of the gate/up GEMM (the pre-activations are only written
+        // when a backward pass will read them)
+        void *gu = p->bwd ? l.up : nullptr;
+        if (m.dec && dt == MS_BF16 && gemm_swiglu_supported(m.n, m.f, m.d, l.h2, m.d, w.w_up, m.d, l.act, m.f, gu, m.dup)) {
+            MS_TRY(gemm_swiglu(m.n, m.f, m.d, l.h2, m.d, w.w_up, m.d, l.act, m.f, gu, m.dup, s));
+        } else {
+            MS_TRY(linear(l.h2, m.d, w.w_up, m.dec ? nullptr : w.b_up, m.dup, l.up, nullptr));
+            MS_TRY(ms_k_act_forward(m.dec ? 0 : 1, dt, m.n, m.f, l.up, l.act, s));
+        }
         MS_TRY(linear(l.act, m.f, w.w_down, m.dec ? nullptr : w.b_down, m.d, y, l.x2));
         return MS_OK;
     }
