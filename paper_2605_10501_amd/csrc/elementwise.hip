@@ -26,7 +26,9 @@ template <class TX, int V> __device__ __forceinline__ void load_row_vec(const TX
     }
 }
 
-template <class T, class TX, int KIND>
+// NC = 16-byte vectors of the row that a lane keeps in registers (1, 2, 4 or kMaxCache; the caller picks the
+// smallest that covers the row, which keeps the register count and with it the occupancy right for each width).
+template <class T, class TX, int KIND, int NC>
 __global__ __launch_bounds__(256) void norm_fwd_kernel(const TX *__restrict__ x, const T *__restrict__ g,
                                                         const T *__restrict__ b, T *__restrict__ y,
                                                         float *__restrict__ mean, float *__restrict__ rstd,
@@ -38,10 +40,10 @@ __global__ __launch_bounds__(256) void norm_fwd_kernel(const TX *__restrict__ x,
     const TX *xr = x + (size_t)row * d;
     T *yr = y + (size_t)row * d;
     const int nvec = d / V;
-    float cache[kMaxCache][V];
+    float cache[NC][V];
     float s = 0.f, ss = 0.f;
 #pragma unroll
-    for (int i = 0; i < kMaxCache; ++i) {
+    for (int i = 0; i < NC; ++i) {
         int idx = lane + 64 * i;
         if (idx < nvec) {
             load_row_vec<TX, V>(xr + (size_t)idx * V, cache[i]);
@@ -52,7 +54,7 @@ __global__ __launch_bounds__(256) void norm_fwd_kernel(const TX *__restrict__ x,
             }
         }
     }
-    for (int idx = lane + 64 * kMaxCache; idx < nvec; idx += 64) {
+    for (int idx = lane + 64 * NC; idx < nvec; idx += 64) {
         float t[V];
         load_row_vec<TX, V>(xr + (size_t)idx * V, t);
 #pragma unroll
@@ -66,7 +68,7 @@ __global__ __launch_bounds__(256) void norm_fwd_kernel(const TX *__restrict__ x,
         mu = wave_sum(s) / d;
         float sq = 0.f;  // second pass over the cached row: sum (x - mu)^2
 #pragma unroll
-        for (int i = 0; i < kMaxCache; ++i) {
+        for (int i = 0; i < NC; ++i) {
             int idx = lane + 64 * i;
             if (idx < nvec) {
 #pragma unroll
@@ -76,7 +78,7 @@ __global__ __launch_bounds__(256) void norm_fwd_kernel(const TX *__restrict__ x,
                 }
             }
         }
-        for (int idx = lane + 64 * kMaxCache; idx < nvec; idx += 64) {
+        for (int idx = lane + 64 * NC; idx < nvec; idx += 64) {
             float t[V];
             load_row_vec<TX, V>(xr + (size_t)idx * V, t);
 #pragma unroll
@@ -106,11 +108,11 @@ __global__ __launch_bounds__(256) void norm_fwd_kernel(const TX *__restrict__ x,
         stv(yr + (size_t)idx * V, out);
     };
 #pragma unroll
-    for (int i = 0; i < kMaxCache; ++i) {
+    for (int i = 0; i < NC; ++i) {
         int idx = lane + 64 * i;
         if (idx < nvec) emit(idx, cache[i]);
     }
-    for (int idx = lane + 64 * kMaxCache; idx < nvec; idx += 64) {
+    for (int idx = lane + 64 * NC; idx < nvec; idx += 64) {
         float t[V];
         load_row_vec<TX, V>(xr + (size_t)idx * V, t);
         emit(idx, t);
@@ -119,22 +121,24 @@ __global__ __launch_bounds__(256) void norm_fwd_kernel(const TX *__restrict__ x,
 
 // ------------------------------------------------------------------ norm backward
 // One wave per row, rows strided over the grid; each lane keeps the dg (and db) sums of its
-// columns in registers and finally writes one partial row per wave.
-template <class T, class TX, int KIND>
+// columns in registers; the four waves of a workgroup add theirs up through LDS and write one
+// partial row per workgroup.  NC as in the forward kernel.
+template <class T, class TX, int KIND, int NC>
 __global__ __launch_bounds__(256) void norm_bwd_kernel(const T *__restrict__ dy, const TX *__restrict__ x,
                                                         const T *__restrict__ g, const float *__restrict__ mean,
                                                         const float *__restrict__ rstd, const T *__restrict__ add,
                                                         T *__restrict__ dx, float *__restrict__ part_g,
                                                         float *__restrict__ part_b, int n, int d) {
     constexpr int V = Vec16<T>::N;
-    const int lane = threadIdx.x & 63;
-    const int w = blockIdx.x * 4 + (threadIdx.x >> 6);
+    __shared__ float red[3][64 * NC * V];
+    const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
+    const int w = blockIdx.x * 4 + wv;
     const int nw = gridDim.x * 4;
     const int nvec = d / V;
-    float accg[kMaxCache][V], accb[KIND == 1 ? kMaxCache : 1][V];
-    Vec16<T> gv[kMaxCache];
+    float accg[NC][V], accb[KIND == 1 ? NC : 1][V];
+    Vec16<T> gv[NC];
 #pragma unroll
-    for (int i = 0; i < kMaxCache; ++i) {
+    for (int i = 0; i < NC; ++i) {
         int idx = lane + 64 * i;
         if (idx < nvec) gv[i] = ldv(g + (size_t)idx * V);
 #pragma unroll
@@ -147,11 +151,11 @@ __global__ __launch_bounds__(256) void norm_bwd_kernel(const T *__restrict__ dy,
         const size_t ro = (size_t)row * d;
         const float r = rstd[row];
         const float mu = KIND == 1 ? mean[row] : 0.f;
-        float xh[kMaxCache][V];
-        Vec16<T> dv[kMaxCache];
+        float xh[NC][V];
+        Vec16<T> dv[NC];
         float c1 = 0.f, c2 = 0.f;
 #pragma unroll
-        for (int i = 0; i < kMaxCache; ++i) {
+        for (int i = 0; i < NC; ++i) {
             int idx = lane + 64 * i;
             if (idx < nvec) {
                 load_row_vec<TX, V>(x + ro + (size_t)idx * V, xh[i]);
@@ -171,7 +175,7 @@ __global__ __launch_bounds__(256) void norm_bwd_kernel(const T *__restrict__ dy,
         c1 = wave_sum(c1) / d;
         c2 = KIND == 1 ? wave_sum(c2) / d : 0.f;
 #pragma unroll
-        for (int i = 0; i < kMaxCache; ++i) {
+        for (int i = 0; i < NC; ++i) {
             int idx = lane + 64 * i;
             if (idx < nvec) {
                 Vec16<T> av, out;
@@ -187,17 +191,32 @@ __global__ __launch_bounds__(256) void norm_bwd_kernel(const T *__restrict__ dy,
             }
         }
     }
+    // waves 1..3 park their sums in LDS, wave 0 adds them and writes the workgroup's partial row
+    auto reduce_and_store = [&](float (*acc)[V], float *part) {
+        if (wv > 0) {
 #pragma unroll
-    for (int i = 0; i < kMaxCache; ++i) {
-        int idx = lane + 64 * i;
-        if (idx < nvec) {
+            for (int i = 0; i < NC; ++i)
 #pragma unroll
-            for (int e = 0; e < V; ++e) {
-                part_g[(size_t)w * d + idx * V + e] = accg[i][e];
-                if constexpr (KIND == 1) part_b[(size_t)w * d + idx * V + e] = accb[i][e];
+                for (int e = 0; e < V; ++e) red[wv - 1][(i * V + e) * 64 + lane] = acc[i][e];
+        }
+        __syncthreads();
+        if (wv == 0) {
+#pragma unroll
+            for (int i = 0; i < NC; ++i) {
+                int idx = lane + 64 * i;
+                if (idx < nvec) {
+#pragma unroll
+                    for (int e = 0; e < V; ++e) {
+                        const int k = (i * V + e) * 64 + lane;
+                        part[(size_t)blockIdx.x * d + idx * V + e] = acc[i][e] + red[0][k] + red[1][k] + red[2][k];
+                    }
+                }
             }
         }
-    }
+        __syncthreads();
+    };
+    reduce_and_store(accg, part_g);
+    if constexpr (KIND == 1) reduce_and_store(accb, part_b);
 }
 
 // out[j] += sum_p part[p, j]; block = 32 columns x 32 row lanes (many short dependent-load chains
@@ -441,11 +460,20 @@ extern "C" ms_status ms_k_norm_forward(int32_t kind, int32_t dtype, int32_t x_fp
     hipStream_t s = (hipStream_t)stream;
     const bool xf = x_fp32 || dtype == MS_F32;
     ProfScope ps(4, (double)n * d * ((xf ? 4 : 2) + (dtype == MS_BF16 ? 2 : 4)), s);
-#define NORM_FWD(T, TX, K) norm_fwd_kernel<T, TX, K><<<ms_cdiv(n, 4), 256, 0, s>>>((const TX *)x, (const T *)g, (const T *)b, (T *)y, mean, rstd, n, d, eps)
+    const int nc = ms_cdiv(d / (dtype == MS_BF16 ? 8 : 4), 64);
+#define NORM_FWD_NC(T, TX, K, NC) norm_fwd_kernel<T, TX, K, NC><<<ms_cdiv(n, 4), 256, 0, s>>>((const TX *)x, (const T *)g, (const T *)b, (T *)y, mean, rstd, n, d, eps)
+#define NORM_FWD(T, TX, K)                                   \
+    do {                                                     \
+        if (nc <= 1) NORM_FWD_NC(T, TX, K, 1);               \
+        else if (nc <= 2) NORM_FWD_NC(T, TX, K, 2);          \
+        else if (nc <= 4) NORM_FWD_NC(T, TX, K, 4);          \
+        else NORM_FWD_NC(T, TX, K, kMaxCache);               \
+    } while (0)
     if (dtype == MS_F32) { if (kind == 1) NORM_FWD(float, float, 1); else NORM_FWD(float, float, 0); }
     else if (xf) { if (kind == 1) NORM_FWD(bf16_t, float, 1); else NORM_FWD(bf16_t, float, 0); }
     else { if (kind == 1) NORM_FWD(bf16_t, bf16_t, 1); else NORM_FWD(bf16_t, bf16_t, 0); }
 #undef NORM_FWD
+#undef NORM_FWD_NC
     MS_LAUNCH_CHECK();
     return MS_OK;
 }
@@ -474,20 +502,29 @@ extern "C" ms_status ms_k_norm_backward(int32_t kind, int32_t dtype, int32_t x_f
     hipStream_t s = (hipStream_t)stream;
     float *pg = (float *)scratch;
     float *pb = (float *)((char *)scratch + ms_align_up((size_t)kPartialRows * d * sizeof(float)));
-    const int grid = n / 4 < 1 ? 1 : (n / 4 > kPartialRows / 4 ? kPartialRows / 4 : n / 4);
+    const int grid = n / 4 < 1 ? 1 : (n / 4 > kPartialRows ? kPartialRows : n / 4);   // one partial row per workgroup
+    const int nc = ms_cdiv(d / V, 64);
     {
     const bool xf = x_fp32 || dtype == MS_F32;
     const double es = dtype == MS_BF16 ? 2 : 4;
     ProfScope ps(5, (double)n * d * ((xf ? 4 : 2) + (add ? 3.0 : 2.0) * es), s);
-#define NORM_BWD(T, TX, K) norm_bwd_kernel<T, TX, K><<<grid, 256, 0, s>>>((const T *)dy, (const TX *)x, (const T *)g, mean, rstd, (const T *)add, (T *)dx, pg, pb, n, d)
+#define NORM_BWD_NC(T, TX, K, NC) norm_bwd_kernel<T, TX, K, NC><<<grid, 256, 0, s>>>((const T *)dy, (const TX *)x, (const T *)g, mean, rstd, (const T *)add, (T *)dx, pg, pb, n, d)
+#define NORM_BWD(T, TX, K)                                   \
+    do {                                                     \
+        if (nc <= 1) NORM_BWD_NC(T, TX, K, 1);               \
+        else if (nc <= 2) NORM_BWD_NC(T, TX, K, 2);          \
+        else if (nc <= 4) NORM_BWD_NC(T, TX, K, 4);          \
+        else NORM_BWD_NC(T, TX, K, kMaxCache);               \
+    } while (0)
     if (dtype == MS_F32) { if (kind == 1) NORM_BWD(float, float, 1); else NORM_BWD(float, float, 0); }
     else if (xf) { if (kind == 1) NORM_BWD(bf16_t, float, 1); else NORM_BWD(bf16_t, float, 0); }
     else { if (kind == 1) NORM_BWD(bf16_t, bf16_t, 1); else NORM_BWD(bf16_t, bf16_t, 0); }
 #undef NORM_BWD
+#undef NORM_BWD_NC
     }
     MS_LAUNCH_CHECK();
-    MS_TRY(reduce_partials(pg, grid * 4, d, dg, s));
-    if (kind == 1) MS_TRY(reduce_partials(pb, grid * 4, d, db, s));
+    MS_TRY(reduce_partials(pg, grid, d, dg, s));
+    if (kind == 1) MS_TRY(reduce_partials(pb, grid, d, db, s));
     return MS_OK;
 }
 
