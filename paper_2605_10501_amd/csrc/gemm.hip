@@ -800,18 +800,33 @@ extern "C" ms_status ms_k_gemm(int32_t dtype, int32_t trans_a, int32_t trans_b, 
     const long tiles256 = (long)ms_cdiv(M, 256) * ms_cdiv(N, 256), tiles128 = (long)ms_cdiv(M, 128) * ms_cdiv(N, 128);
     const double eff256 = (double)tiles256 / (double)(ms_cdiv(tiles256, 256) * 256L);
     const double eff128 = (double)tiles128 / (double)(ms_cdiv(tiles128, 512) * 512L);
-    const bool big = fast && (forced > 0 ? forced == 256 : (tiles256 >= 192 && 1.25 * eff256 > eff128));
-    const int BM = big ? 256 : 128, BN = BM;
-    p.tiles_m = ms_cdiv(M, BM); p.tiles_n = ms_cdiv(N, BN);
+    bool big = fast && (forced > 0 ? forced == 256 : (tiles256 >= 192 && 1.25 * eff256 > eff128));
     const int kt_total = ms_cdiv(K, BK) < 1 ? 1 : ms_cdiv(K, BK);
     int splits = split_k;
-    if (splits <= 0) {  // automatic: only when accumulating into fp32 and the grid is small
+    if (splits <= 0) {  // automatic: only when accumulating into fp32 (weight gradients: small M x N, long K)
         splits = 1;
-        if (accumulate && c_fp32) {
-            const int tiles = p.tiles_m * p.tiles_n;
+        if (accumulate && c_fp32 && fast) {
+            // Cost model fitted to measurements on wgrad shapes (microseconds): rounds of resident workgroups
+            // x (K tiles per split x time per K tile + fixed part) + one pass of fp32 atomics over C per split
+            // at ~2 TB/s.  256 x 256: one workgroup per CU, 1.57 us per K tile; 128 x 128: two per CU, 1.07 us.
+            double best = 1e30;
+            for (int t256 = 0; t256 <= 1; ++t256) {
+                if (forced > 0 && (forced == 256) != (t256 == 1)) continue;
+                const long tiles = t256 ? tiles256 : tiles128, slots = t256 ? 256 : 512;
+                const double tk = t256 ? 1.57 : 1.07, fix = t256 ? 12.0 : 5.0;
+                for (int sp = 1; sp <= 8 && (sp == 1 || kt_total / sp >= 8); ++sp) {
+                    const double rounds = (double)ms_cdiv(tiles * sp, slots);
+                    const double est = rounds * (ms_cdiv(kt_total, sp) * tk + fix) + (sp > 1 ? 4.0e-6 * M * N * sp / 2.0 : 0.0);
+                    if (est < best) { best = est; splits = sp; big = t256 == 1; }
+                }
+            }
+        } else if (accumulate && c_fp32) {
+            const int tiles = (int)tiles128;
             while (tiles * splits < 512 && kt_total / (splits * 2) >= 8) splits *= 2;
         }
     }
+    const int BM = big ? 256 : 128, BN = BM;
+    p.tiles_m = ms_cdiv(M, BM); p.tiles_n = ms_cdiv(N, BN);
     if (splits > 1 && !(accumulate && c_fp32)) return ms_fail(MS_ERR_INVALID_ARG, "gemm: split_k needs accumulate into fp32");
     if (splits > kt_total) splits = kt_total;
     p.k_tiles_per_split = ms_cdiv(kt_total, splits);
