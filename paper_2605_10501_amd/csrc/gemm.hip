@@ -41,7 +41,7 @@ struct GemmParams {
     // KD epilogues (EPI != 0): the tile holds student logits zs; zt = teacher logits of the same chunk
     const float *kd_zt;      // [M, kd_ldz] fp32
     long kd_ldz;
-    float *kd_stats;         // EPI_KD_DZ: [M][8] per-token statistics (lse_t at 5, lse_s at 6), read
+    float *kd_stats;         // EPI_KD_DZ: [M][8] per-token statistics (lse_t at 6, lse_s at 7), read
     float *kd_part;          // EPI_KD_STATS: [M][kd_nparts][8] partial statistics per 64-column strip, written
     int kd_nparts;
     float kd_inv_t, kd_coef;
@@ -461,114 +461,67 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_bf16_fast_kernel(GemmParams
         }
         return;
     }
-    if constexpr (EPI == EPI_KD_DZ || EPI == EPI_KD_STATS) {
-        // Same staging through LDS as the vector epilogue below (a lane ends up with 4 consecutive columns
-        // of a row), then, instead of storing the student logits zs:
-        //   EPI_KD_DZ:    dz = coef * (exp(zs/T - lse_s) - exp(zt/T - lse_t)) -> C (storage dtype)
-        //   EPI_KD_STATS: per row, over this wave's 64 columns: max and sum of exponentials of zt/T and
-        //                 zs/T and the cross term sum e^{zt/T - m_t} (zt - zs)/T -> kd_part
-        static_assert(WTN == 64 && !TA && !TB, "KD epilogues are built for the K-contiguous layout");
-        constexpr int WPA = BM / 64;
-        float *stg = (float *)((wave / WPA) ? As1 : As0) + (wave % WPA) * 2048;
-        const int prow = lane >> 4, pcol = (lane & 15) * 4;
-        const int colg = n0 + wn * WTN + pcol;
-        const bool cok = colg < p.N;
-        const __amdgpu_buffer_rsrc_t rz = make_rsrc(p.kd_zt, (long)p.M * p.kd_ldz * 4);
-        const float it = p.kd_inv_t;
-#pragma unroll
-        for (int i = 0; i < MI; ++i) {
-#pragma unroll
-            for (int j = 0; j < NI; ++j)
-#pragma unroll
-                for (int r = 0; r < 16; ++r) {
-                    const int row = 8 * (r >> 2) + 4 * fhalf + (r & 3);
-                    stg[row * 64 + ((j * 32 + frow) ^ (fhalf << 5))] = acc[i][j][r] * p.alpha;
-                }
-#pragma unroll
-            for (int ps = 0; ps < 8; ++ps) {
-                const int row = ps * 4 + prow;
-                const float4 t = *(const float4 *)(stg + row * 64 + (pcol ^ (((row >> 2) & 1) << 5)));
-                const float zs[4] = {t.x, t.y, t.z, t.w};
-                const long rowg = m0 + wm * WTM + i * 32 + row;
-                const bool rok = rowg < p.M;
-                const u32x4 q = __builtin_amdgcn_raw_buffer_load_b128(rz, cok ? (unsigned)((rowg * p.kd_ldz + colg) * 4) : kOob, 0, 0);
-                float zt[4];
-#pragma unroll
-                for (int e = 0; e < 4; ++e) zt[e] = __uint_as_float(q[e]);
-                if constexpr (EPI == EPI_KD_DZ) {
-                    const float lse_t = rok ? p.kd_stats[rowg * 8 + 5] : 0.f, lse_s = rok ? p.kd_stats[rowg * 8 + 6] : 0.f;
-                    float v[4];
-#pragma unroll
-                    for (int e = 0; e < 4; ++e) v[e] = p.kd_coef * (__expf(zs[e] * it - lse_s) - __expf(zt[e] * it - lse_t));
-                    const unsigned co = cok ? (unsigned)((rowg * p.ldc + colg) * esz) : kOob;
-                    if (p.c_fp32) {
-                        u32x4 w;
-#pragma unroll
-                        for (int e = 0; e < 4; ++e) w[e] = __builtin_bit_cast(unsigned, v[e]);
-                        __builtin_amdgcn_raw_buffer_store_b128(w, rc, co, 0, 0);
-                    } else {
-                        u32x2 w;
-                        w[0] = (unsigned)__builtin_bit_cast(unsigned short, (bf16_t)v[0]) | ((unsigned)__builtin_bit_cast(unsigned short, (bf16_t)v[1]) << 16);
-                        w[1] = (unsigned)__builtin_bit_cast(unsigned short, (bf16_t)v[2]) | ((unsigned)__builtin_bit_cast(unsigned short, (bf16_t)v[3]) << 16);
-                        __builtin_amdgcn_raw_buffer_store_b64(w, rc, co, 0, 0);
-                    }
-                } else {
-                    // the 16 lanes that share a row reduce with xor-shuffles inside their group
-                    float mt = cok ? fmaxf(fmaxf(zt[0], zt[1]), fmaxf(zt[2], zt[3])) : -INFINITY;
-                    float ms = cok ? fmaxf(fmaxf(zs[0], zs[1]), fmaxf(zs[2], zs[3])) : -INFINITY;
-#pragma unroll
-                    for (int o = 1; o < 16; o <<= 1) {
-                        mt = fmaxf(mt, __shfl_xor(mt, o, 64));
-                        ms = fmaxf(ms, __shfl_xor(ms, o, 64));
-                    }
-                    mt *= it; ms *= it;                                   // T > 0
-                    const float mtu = mt == -INFINITY ? 0.f : mt, msu = ms == -INFINITY ? 0.f : ms;
-                    float st = 0.f, ss = 0.f, ac = 0.f;
-                    if (cok) {
-#pragma unroll
-                        for (int e = 0; e < 4; ++e) {
-                            const float et = __expf(zt[e] * it - mtu);
-                            st += et;
-                            ac += et * (zt[e] - zs[e]) * it;
-                            ss += __expf(zs[e] * it - msu);
-                        }
-                    }
-#pragma unroll
-                    for (int o = 1; o < 16; o <<= 1) {
-                        st += __shfl_xor(st, o, 64);
-                        ss += __shfl_xor(ss, o, 64);
-                        ac += __shfl_xor(ac, o, 64);
-                    }
-                    if ((lane & 15) == 0 && rok && n0 + wn * WTN < p.N) {
-                        float *o = p.kd_part + ((long)rowg * p.kd_nparts + (n0 + wn * WTN) / 64) * 8;
-                        *(float4 *)o = make_float4(mt, st, ms, ss);
-                        o[4] = ac;
-                    }
-                }
-            }
-        }
-        return;
-    }
-    if (p.vec_epilogue) {
-        // Each wave passes its accumulators through LDS, 32 rows at a time, to turn the MFMA layout
-        // (a lane owns one column) into rows: a lane then handles 4 consecutive columns of a row, so
-        // residual reads and C writes are 8..16 bytes per lane and 128..256 contiguous bytes per row.
+    // ---- vector epilogues.  Each wave passes its accumulators through LDS, 32 rows at a time, to turn the
+    // MFMA layout (a lane owns one column) into rows: a lane then handles 4 consecutive columns of a row, so
+    // global reads and writes are 8..16 bytes per lane and 128..256 contiguous bytes per row.  What the
+    // epilogue reads from memory for a 32-row block (fp32/bf16 residual, C when accumulating, teacher logits)
+    // is fetched one block ahead into registers: the loads of block i+1 are issued before the stores of
+    // block i, so no pass waits for a store or for its own load's full latency.
+    if (EPI != EPI_NONE || p.vec_epilogue) {
         static_assert(WTN == 64, "staging assumes 64-column wave tiles");
         constexpr int WPA = BM / 64;                       // waves sharing one of the (now idle) A buffers
         float *stg = (float *)((wave / WPA) ? As1 : As0) + (wave % WPA) * 2048;
         const int prow = lane >> 4, pcol = (lane & 15) * 4;
         const int colg = n0 + col_base(pcol >> 5) + (pcol & 31);
         const bool cok = colg < p.N;
+        // the prefetched stream: KD -> teacher logits (fp32); else residual (fp32 or bf16); else C (accumulate)
+        const bool aux_res = EPI == EPI_NONE && p.residual != nullptr;
+        const bool aux_c = EPI == EPI_NONE && !aux_res && p.accumulate && p.c_fp32;
+        const bool has_aux = EPI != EPI_NONE || aux_res || aux_c;
+        const bool aux4 = EPI != EPI_NONE || aux_c || p.res_fp32;                  // 4-byte elements
+        const long aux_ld = EPI != EPI_NONE ? p.kd_ldz : (aux_res ? p.ldr : p.ldc);
+        const __amdgpu_buffer_rsrc_t ra_ = EPI != EPI_NONE ? make_rsrc(p.kd_zt, (long)p.M * p.kd_ldz * 4) : (aux_res ? rr : rc);
+        u32x4 aux[2][8];
+        float2 lsev[2][8];                                                         // EPI_KD_DZ: (lse_t, lse_s) of the row
+        auto prefetch = [&](int i, u32x4 *dst, float2 *ldst) {
+#pragma unroll
+            for (int ps = 0; ps < 8; ++ps) {
+                const long rowg = m0 + row_base(i) + ps * 4 + prow;
+                const unsigned off = cok ? (unsigned)((rowg * aux_ld + colg) * (aux4 ? 4 : 2)) : kOob;
+                if (aux4) dst[ps] = __builtin_amdgcn_raw_buffer_load_b128(ra_, off, 0, 0);
+                else {
+                    const u32x2 q = __builtin_amdgcn_raw_buffer_load_b64(ra_, off, 0, 0);
+                    dst[ps][0] = q[0]; dst[ps][1] = q[1];
+                }
+                if constexpr (EPI == EPI_KD_DZ) ldst[ps] = rowg < p.M ? *(const float2 *)(p.kd_stats + rowg * 8 + 6) : make_float2(0.f, 0.f);
+            }
+        };
         float bv[4] = {0.f, 0.f, 0.f, 0.f};
-        if (bias && cok) {
+        if (EPI == EPI_NONE && bias && cok) {
             const uint2 b2 = *(const uint2 *)(bias + colg);
             bv[0] = (float)__builtin_bit_cast(bf16_t, (unsigned short)(b2.x & 0xffff));
             bv[1] = (float)__builtin_bit_cast(bf16_t, (unsigned short)(b2.x >> 16));
             bv[2] = (float)__builtin_bit_cast(bf16_t, (unsigned short)(b2.y & 0xffff));
             bv[3] = (float)__builtin_bit_cast(bf16_t, (unsigned short)(b2.y >> 16));
         }
+        auto store4 = [&](const float *v, unsigned co) {
+            if (p.c_fp32) {
+                u32x4 w;
+#pragma unroll
+                for (int e = 0; e < 4; ++e) w[e] = __builtin_bit_cast(unsigned, v[e]);
+                __builtin_amdgcn_raw_buffer_store_b128(w, rc, co, 0, 0);
+            } else {
+                u32x2 w;
+                w[0] = (unsigned)__builtin_bit_cast(unsigned short, (bf16_t)v[0]) | ((unsigned)__builtin_bit_cast(unsigned short, (bf16_t)v[1]) << 16);
+                w[1] = (unsigned)__builtin_bit_cast(unsigned short, (bf16_t)v[2]) | ((unsigned)__builtin_bit_cast(unsigned short, (bf16_t)v[3]) << 16);
+                __builtin_amdgcn_raw_buffer_store_b64(w, rc, co, 0, 0);
+            }
+        };
+        const float it = p.kd_inv_t;
+        if (has_aux) prefetch(0, aux[0], lsev[0]);
 #pragma unroll
         for (int i = 0; i < MI; ++i) {
+            if (has_aux && i + 1 < MI) prefetch(i + 1, aux[(i + 1) & 1], lsev[(i + 1) & 1]);
             // accumulators -> LDS [32 rows][64 columns] fp32; column bit 5 is flipped for rows 4..7 (mod 8)
             // so that the two half-waves (rows 4 apart) use different banks
 #pragma unroll
@@ -582,38 +535,76 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_bf16_fast_kernel(GemmParams
             for (int ps = 0; ps < 8; ++ps) {
                 const int row = ps * 4 + prow;
                 const float4 t = *(const float4 *)(stg + row * 64 + (pcol ^ (((row >> 2) & 1) << 5)));
-                float v[4] = {t.x + bv[0], t.y + bv[1], t.z + bv[2], t.w + bv[3]};
                 const long rowg = m0 + row_base(i) + row;
-                if (p.residual) {
-                    const unsigned ro = cok ? (unsigned)((rowg * p.ldr + colg) * rsz) : kOob;
-                    if (p.res_fp32) {
-                        const u32x4 q = __builtin_amdgcn_raw_buffer_load_b128(rr, ro, 0, 0);
-#pragma unroll
-                        for (int e = 0; e < 4; ++e) v[e] += __uint_as_float(q[e]);
-                    } else {
-                        const u32x2 q = __builtin_amdgcn_raw_buffer_load_b64(rr, ro, 0, 0);
-                        v[0] += (float)__builtin_bit_cast(bf16_t, (unsigned short)(q[0] & 0xffff));
-                        v[1] += (float)__builtin_bit_cast(bf16_t, (unsigned short)(q[0] >> 16));
-                        v[2] += (float)__builtin_bit_cast(bf16_t, (unsigned short)(q[1] & 0xffff));
-                        v[3] += (float)__builtin_bit_cast(bf16_t, (unsigned short)(q[1] >> 16));
-                    }
-                }
+                const u32x4 q = aux[i & 1][ps];
                 const unsigned co = cok ? (unsigned)((rowg * p.ldc + colg) * esz) : kOob;
-                if (p.c_fp32) {
-                    if (p.accumulate) {
-                        const u32x4 q = __builtin_amdgcn_raw_buffer_load_b128(rc, co, 0, 0);
+                if constexpr (EPI == EPI_NONE) {
+                    float v[4] = {t.x + bv[0], t.y + bv[1], t.z + bv[2], t.w + bv[3]};
+                    if (aux_res || aux_c) {
+                        if (aux4) {
 #pragma unroll
-                        for (int e = 0; e < 4; ++e) v[e] += __uint_as_float(q[e]);
+                            for (int e = 0; e < 4; ++e) v[e] += __uint_as_float(q[e]);
+                        } else {
+                            v[0] += (float)__builtin_bit_cast(bf16_t, (unsigned short)(q[0] & 0xffff));
+                            v[1] += (float)__builtin_bit_cast(bf16_t, (unsigned short)(q[0] >> 16));
+                            v[2] += (float)__builtin_bit_cast(bf16_t, (unsigned short)(q[1] & 0xffff));
+                            v[3] += (float)__builtin_bit_cast(bf16_t, (unsigned short)(q[1] >> 16));
+                        }
                     }
-                    u32x4 w;
+                    if (aux_res && p.accumulate && p.c_fp32) {        // both a residual and += : C is read in place
+                        const u32x4 c4 = __builtin_amdgcn_raw_buffer_load_b128(rc, co, 0, 0);
 #pragma unroll
-                    for (int e = 0; e < 4; ++e) w[e] = __builtin_bit_cast(unsigned, v[e]);
-                    __builtin_amdgcn_raw_buffer_store_b128(w, rc, co, 0, 0);
+                        for (int e = 0; e < 4; ++e) v[e] += __uint_as_float(c4[e]);
+                    }
+                    store4(v, co);
                 } else {
-                    u32x2 w;
-                    w[0] = (unsigned)__builtin_bit_cast(unsigned short, (bf16_t)v[0]) | ((unsigned)__builtin_bit_cast(unsigned short, (bf16_t)v[1]) << 16);
-                    w[1] = (unsigned)__builtin_bit_cast(unsigned short, (bf16_t)v[2]) | ((unsigned)__builtin_bit_cast(unsigned short, (bf16_t)v[3]) << 16);
-                    __builtin_amdgcn_raw_buffer_store_b64(w, rc, co, 0, 0);
+                    // the tile holds student logits zs; q = teacher logits zt of the same elements
+                    const float zs[4] = {t.x, t.y, t.z, t.w};
+                    float zt[4];
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) zt[e] = __uint_as_float(q[e]);
+                    if constexpr (EPI == EPI_KD_DZ) {
+                        // dz = coef * (exp(zs/T - lse_s) - exp(zt/T - lse_t)) -> C (storage dtype)
+                        const float lse_t = lsev[i & 1][ps].x, lse_s = lsev[i & 1][ps].y;
+                        float v[4];
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) v[e] = p.kd_coef * (__expf(zs[e] * it - lse_s) - __expf(zt[e] * it - lse_t));
+                        store4(v, co);
+                    } else {
+                        // per row, over this wave's 64 columns: max and sum of exponentials of zt/T and zs/T and
+                        // the cross term sum e^{zt/T - m_t} (zt - zs)/T -> kd_part; the 16 lanes that share a
+                        // row reduce with xor-shuffles inside their group
+                        float mt = cok ? fmaxf(fmaxf(zt[0], zt[1]), fmaxf(zt[2], zt[3])) : -INFINITY;
+                        float ms = cok ? fmaxf(fmaxf(zs[0], zs[1]), fmaxf(zs[2], zs[3])) : -INFINITY;
+#pragma unroll
+                        for (int o = 1; o < 16; o <<= 1) {
+                            mt = fmaxf(mt, __shfl_xor(mt, o, 64));
+                            ms = fmaxf(ms, __shfl_xor(ms, o, 64));
+                        }
+                        mt *= it; ms *= it;                                   // T > 0
+                        const float mtu = mt == -INFINITY ? 0.f : mt, msu = ms == -INFINITY ? 0.f : ms;
+                        float st = 0.f, ss = 0.f, ac = 0.f;
+                        if (cok) {
+#pragma unroll
+                            for (int e = 0; e < 4; ++e) {
+                                const float et = __expf(zt[e] * it - mtu);
+                                st += et;
+                                ac += et * (zt[e] - zs[e]) * it;
+                                ss += __expf(zs[e] * it - msu);
+                            }
+                        }
+#pragma unroll
+                        for (int o = 1; o < 16; o <<= 1) {
+                            st += __shfl_xor(st, o, 64);
+                            ss += __shfl_xor(ss, o, 64);
+                            ac += __shfl_xor(ac, o, 64);
+                        }
+                        if ((lane & 15) == 0 && rowg < p.M && n0 + wn * WTN < p.N) {
+                            float *o = p.kd_part + ((long)rowg * p.kd_nparts + (n0 + wn * WTN) / 64) * 8;
+                            *(float4 *)o = make_float4(mt, st, ms, ss);
+                            o[4] = ac;
+                        }
+                    }
                 }
             }
         }

@@ -14,7 +14,7 @@
 
 namespace {
 
-constexpr int kStat = 8;  // floats per token: m_t, s_t, m_s, s_s, A, lse_t, lse_s, unused
+constexpr int kStat = 8;  // floats per token: m_t, s_t, m_s, s_s, A, unused, lse_t, lse_s
 
 __device__ __forceinline__ float block_max(float v, float *sm) {
     v = wave_max(v);
@@ -95,8 +95,8 @@ __global__ __launch_bounds__(1024) void kd_finalize_kernel(float *__restrict__ s
         const float lse_t = st[0] + __logf(st[1]);
         const float lse_s = st[2] + __logf(st[3]);
         const float kl = st[4] / st[1] - lse_t + lse_s;
-        st[5] = lse_t;
-        st[6] = lse_s;
+        st[6] = lse_t;
+        st[7] = lse_s;
         if (kl_tok) kl_tok[t] = kl;
         acc += kl;
     }
@@ -111,7 +111,7 @@ __global__ __launch_bounds__(256) void kd_dz_kernel(const float *__restrict__ zt
     const long t = blockIdx.y;
     const int c4 = (blockIdx.x * 256 + threadIdx.x) * 4;
     if (c4 >= cw) return;
-    const float lse_t = stats[t * kStat + 5], lse_s = stats[t * kStat + 6];
+    const float lse_t = stats[t * kStat + 6], lse_s = stats[t * kStat + 7];
     const float4 a = *(const float4 *)(zt + t * ld + c4), b = *(const float4 *)(zs + t * ld + c4);
     const float av[4] = {a.x, a.y, a.z, a.w}, bv[4] = {b.x, b.y, b.z, b.w};
     T *o = dz + t * ld + c4;
