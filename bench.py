@@ -35,6 +35,10 @@ def model_flops(work):
                 kd=2.0 * n * kd.vocab * (kd.h_teacher + kd.h_student) + 4.0 * n * kd.vocab * kd.h_student)
 
 
+def describe(c):
+    return f"{c.n_layers}L d{c.d_model} {c.n_q_heads}/{c.n_kv_heads} heads hd{c.head_dim} F{c.d_ffn}"
+
+
 def nt_gemm_shapes(work):
     """(M, N, K, out_bytes, residual_bytes) of every A[M,K]*B[N,K]^T launch of one step (decoder sections)."""
     n = work.n_tokens
@@ -136,6 +140,9 @@ def main():
     loss = float(out["loss"].item())
     sec_teacher, _ = timed(teacher, args.steps)
     sec_student, _ = timed(student, args.steps)
+    # the KD head alone (both lm_heads, loss, gradients to the student hidden states and lm_head) on this batch
+    h_s = wl.normal(0, "bench.h_s", (n, kd.h_student), 1.0, 0.0, dt, dev)
+    sec_kd, _ = timed(lambda: B.kd_loss_forward_backward(kd, wt, ws, h_t, h_s, d_w_student=d_ws), args.steps)
 
     # per-kernel durations from HIP events on the launch stream (separate, untimed-for-value steps)
     B.profile_enable(1)
@@ -170,10 +177,11 @@ def main():
         "value": n / sec_step, "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": 1e3 * sec_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16", "data": "synthetic",
-        "config": {"workload": f"{work.name}: mid-size KD step, {n} packed tokens, {batch.n_seqs} sequences "
-                               f"(max {batch.max_seqlen}), teacher 8L d2048 16/4 heads F5504, student 4L d1024 8/2 "
-                               f"heads F2816, vocab 32000, T=2, chunk {kd.chunk}"},
+        "config": {"workload": f"{work.name}: KD step, {n} packed tokens, {batch.n_seqs} sequences (max {batch.max_seqlen}), "
+                               f"teacher {describe(t_cfg)}, student {describe(s_cfg)}, vocab {kd.vocab}, "
+                               f"T={kd.temperature:g}, chunk {kd.chunk}"},
         "teacher_fwd_tokens_per_s": n / sec_teacher, "student_fwd_bwd_kd_tokens_per_s": n / sec_student,
+        "kd_loss_fwd_bwd_tokens_per_s": n / sec_kd, "mfma_frac_kd_loss": fl["kd"] / sec_kd / 1e12 / PEAK_BF16_TFLOPS,
         "model_tflop_per_step": total_flops / 1e12,
         "mfma_frac_whole_step": total_flops / sec_step / 1e12 / PEAK_BF16_TFLOPS,
         "mfma_frac_teacher_fwd": fl["teacher"] / sec_teacher / 1e12 / PEAK_BF16_TFLOPS,
