@@ -152,6 +152,16 @@ def main():
     torch.cuda.synchronize()
     prof = B.profile_read()
     B.profile_enable(0)
+    # what the chip sustains on this machine: register-resident MFMA loop and a plain 1 GiB copy (references beside
+    # the published peaks)
+    sink = torch.zeros(512 * 512, dtype=torch.float32, device=dev)
+    sec_probe, _ = timed(lambda: B.k_mfma_probe(512, 10000, sink), 3)
+    probe_tflops = 512 * 8 * 10000 * 8 * 32768 / sec_probe / 1e12
+    src = torch.ones(1 << 30, dtype=torch.uint8, device=dev)
+    dst = torch.empty_like(src)
+    sec_copy, _ = timed(lambda: B.k_copy(src, dst), 3)
+    copy_gbs = 2.0 * (1 << 30) / sec_copy / 1e9
+    del src, dst, sink
     fl = model_flops(work)
     g_n, g_ms, g_work = prof["gemm_nt"]
     gt_n, gt_ms, gt_work = prof["gemm_t"]
@@ -187,6 +197,7 @@ def main():
         "mfma_frac_teacher_fwd": fl["teacher"] / sec_teacher / 1e12 / PEAK_BF16_TFLOPS,
         "mfma_frac_student_fwd_bwd_kd": (fl["student"] + fl["kd"]) / sec_student / 1e12 / PEAK_BF16_TFLOPS,
         "loss": loss, "logits_to_hidden_ratio": kd.vocab / kd.h_teacher,
+        "measured_references": {"mfma_register_loop_tflops": probe_tflops, "copy_1gib_read_plus_write_gbs": copy_gbs},
         "roofline": {"kernel": "gemm_bf16_fast_kernel (A[M,K] B[N,K]^T, all forward linears and lm_head chunks)",
                      "bound": "mfma", "achieved": achieved, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
                      "frac": achieved / PEAK_BF16_TFLOPS, "traffic": traffic,

@@ -333,6 +333,10 @@ def k_attention_backward(qkv, o, lse, d_o, batch, n_q_heads, n_kv_heads, head_di
     return dqkv
 
 
+def k_mfma_probe(workgroups, iters, sink):
+    _check(lib().ms_k_mfma_probe(workgroups, iters, _p(sink), _stream()))
+
+
 def k_copy(src, dst):
     _check(lib().ms_k_copy(_p(src), _p(dst), C.c_size_t(src.numel() * src.element_size()), _stream()))
     return dst

@@ -913,3 +913,34 @@ ms_status gemm_swiglu(int M, int F, int K, const void *A, long lda, const void *
     MS_LAUNCH_CHECK();
     return MS_OK;
 }
+
+// ------------------------------------------------------------------ matrix-core rate probe
+namespace {
+__global__ __launch_bounds__(512) void mfma_probe_kernel(int iters, float *sink) {
+    f32x16 acc[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[i][r] = 0.f;
+    bf16x8 a, b;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) { a[e] = (bf16_t)(float)(threadIdx.x & 3); b[e] = (bf16_t)(1.f / 64.f); }
+    for (int it = 0; it < iters; ++it) {
+#pragma unroll
+        for (int i = 0; i < 8; ++i) acc[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, acc[i], 0, 0, 0);
+    }
+    float t = 0.f;
+#pragma unroll
+    for (int i = 0; i < 8; ++i)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) t += acc[i][r];
+    sink[(long)blockIdx.x * 512 + threadIdx.x] = t;
+}
+}  // namespace
+
+extern "C" ms_status ms_k_mfma_probe(int32_t workgroups, int32_t iters, float *sink_dev, void *stream) {
+    if (workgroups <= 0 || iters <= 0 || !sink_dev) return ms_fail(MS_ERR_INVALID_ARG, "mfma_probe: bad argument");
+    mfma_probe_kernel<<<workgroups, 512, 0, (hipStream_t)stream>>>(iters, sink_dev);
+    MS_LAUNCH_CHECK();
+    return MS_OK;
+}

@@ -204,3 +204,11 @@ def test_attention_forward_backward(dtype, causal, nq, nkv, hd, cu, sharp):
     check = assert_parity_chain if dtype == torch.bfloat16 else assert_parity
     for name, sl in [("dq", slice(0, nq * hd)), ("dk", slice(nq * hd, (nq + nkv) * hd)), ("dv", slice((nq + nkv) * hd, None))]:
         check(dqkv[:, sl], rnd(ref[:, sl]), tol, name)
+
+
+def test_mfma_probe_counts_what_it_claims():
+    # every accumulator element gains (row % 4) / 4 per MFMA; a lane's 16 rows cover each residue 4 times
+    sink = torch.zeros(4 * 512, dtype=torch.float32, device="cuda")
+    B.k_mfma_probe(4, 10, sink)
+    torch.cuda.synchronize()
+    assert torch.all(sink == 480.0)
