@@ -40,18 +40,24 @@ def describe(c):
 
 
 def nt_gemm_shapes(work):
-    """(M, N, K, out_bytes, residual_bytes) of every A[M,K]*B[N,K]^T launch of one step (decoder sections)."""
+    """(M, N, K, bytes written per output element, bytes read per output element besides A and B) of every
+    A[M,K]*B[N,K]^T launch of one step (decoder sections, bf16 fast path with its fused epilogues)."""
     n = work.n_tokens
     out = []
-    for cfg in (work.teacher, work.student):
+    for cfg, bwd in ((work.teacher, False), (work.student, True)):
         d, f = cfg.d_model, cfg.d_ffn
         qkv = (cfg.n_q_heads + 2 * cfg.n_kv_heads) * cfg.head_dim
-        per_layer = [(n, qkv, d, 2, 0), (n, d, cfg.n_q_heads * cfg.head_dim, 4, 4), (n, 2 * f, d, 2, 0), (n, d, f, 4, 4)]
+        # gate/up + SwiGLU: N = 2F accumulator columns; writes act [n, F] (1 B per accumulator column) and, when a
+        # backward pass follows, the pre-activations [n, 2F] as well
+        per_layer = [(n, qkv, d, 2, 0), (n, d, cfg.n_q_heads * cfg.head_dim, 4, 4), (n, 2 * f, d, 3 if bwd else 1, 0),
+                     (n, d, f, 4, 4)]
         out += per_layer * cfg.n_layers
     kd = work.kd
     for v0 in range(0, kd.vocab, kd.chunk):
         cw = min(kd.chunk, kd.vocab - v0)
-        out += [(n, cw, kd.h_teacher, 4, 0), (n, cw, kd.h_student, 4, 0)] * 2      # statistics pass + recompute
+        # teacher logits stored fp32 in both passes; student logits consumed by their epilogue together with the
+        # teacher's (statistics: nothing but 0.5 B of partials per column; dz: 2 B)
+        out += [(n, cw, kd.h_teacher, 4, 0), (n, cw, kd.h_student, 0.5, 4), (n, cw, kd.h_teacher, 4, 0), (n, cw, kd.h_student, 2, 4)]
     return out
 
 

@@ -152,6 +152,25 @@ ms_status ms_kd_loss_forward_backward(const ms_kd_config *kd, int32_t n_tokens,
                                       void *d_h_student, void *d_w_student,
                                       void *workspace_dev, size_t workspace_bytes, void *stream);
 
+/* Wavefront sample scheduling (Sec. 3.4, Algorithm 1); host code, all pointers are host memory.
+ * tuples[n_samples][6] = (t_f_bc, t_f_c, t_f_ac, t_b_bc, t_b_c, t_b_ac): forward time before / within /
+ * after the critical section, then backward time before (sections behind the critical one in forward
+ * order) / within / after (sections in front of it) the critical section; non-negative, any unit.
+ * ms_schedule_samples: stable sort by t_f_bc, then each remaining sample is inserted at the position
+ * (lowest on ties; makespans within 1e-9 relative are ties) that gives the least simulated makespan; order_out[n_samples] receives sample indices
+ * in execution order, *makespan_out (optional) the simulated makespan.  O(n^3) time.
+ * ms_schedule_makespan: makespan of a given order (a permutation of 0..n-1, else MS_ERR_INVALID_ARG) and
+ * (optional) the time the critical section spends idle before its last job ends.
+ * Timeline model: three serial servers (sections in front of the critical one, the critical section, the
+ * sections behind it); a job starts when its server is free and the previous job on the sample's path
+ * forward-in-front -> critical forward -> behind (forward + backward) -> critical backward ->
+ * backward-in-front is done; the front server runs its forward jobs first; interleave != 0: the critical
+ * section runs forward and backward sample by sample, else all forwards then all backwards. */
+ms_status ms_schedule_samples(int32_t n_samples, const double *tuples, int32_t interleave,
+                              int32_t *order_out, double *makespan_out);
+ms_status ms_schedule_makespan(int32_t n_samples, const double *tuples, const int32_t *order,
+                               int32_t interleave, double *makespan_out, double *critical_idle_out);
+
 /* Host step that orders samples into packed micro-batches (Sec. 3.4 for the ordering
  * role; a sample of length 0 does not activate the section and is dropped, Sec. 2.1).
  * policy 0 keeps the input order, 1 sorts longest first (stable).  Greedy fill: a sample

@@ -217,6 +217,25 @@ def pack_microbatches(lengths, token_budget, policy=0):
     return [order[i] for i in range(offs_l[-1])], offs_l, out
 
 
+def schedule_samples(tuples, interleave=True):
+    """tuples: n x 6 times (Sec. 3.4).  Returns (order, makespan)."""
+    n = len(tuples)
+    flat = (C.c_double * max(6 * n, 1))(*[float(x) for t in tuples for x in t])
+    order, mk = (C.c_int32 * max(n, 1))(), C.c_double(0.0)
+    _check(lib().ms_schedule_samples(n, flat, int(bool(interleave)), order, C.byref(mk)))
+    return [order[i] for i in range(n)], mk.value
+
+
+def schedule_makespan(tuples, order, interleave=True):
+    """Returns (makespan, critical_idle) of executing `tuples` in `order`."""
+    n = len(tuples)
+    flat = (C.c_double * max(6 * n, 1))(*[float(x) for t in tuples for x in t])
+    arr = (C.c_int32 * max(n, 1))(*order)
+    mk, idle = C.c_double(0.0), C.c_double(0.0)
+    _check(lib().ms_schedule_makespan(n, flat, arr, int(bool(interleave)), C.byref(mk), C.byref(idle)))
+    return mk.value, idle.value
+
+
 # ------------------------------------------------------------------ kernel-level entry points
 def k_gemm(a, b, trans_a=False, trans_b=False, c=None, c_fp32=False, accumulate=False, bias=None, residual=None,
            alpha=1.0, split_k=1, dtype=None):
