@@ -158,6 +158,17 @@ def main():
     torch.cuda.synchronize()
     prof = B.profile_read()
     B.profile_enable(0)
+    # teacher micro-batch sweep (Sec. 4.2: a forward-only teacher is under-utilised by small micro-batches):
+    # forward rate and workspace of the teacher section at 1, 2, 4, 8 packed samples of 4096 tokens
+    sweep = []
+    for k in (1, 2, 4, 8):
+        nt = 4096 * k
+        bt = B.Batch([4096 * i for i in range(k + 1)])
+        ids_k = wl.randint(0, "sweep.ids", nt, 0, t_cfg.vocab, dev)
+        need = B.section_workspace_bytes(t_cfg, nt, 4096, False)
+        wsk = B.workspace(need, dev, "sweep")
+        sec_k, _ = timed(lambda: B.section_forward(t_cfg, tw, bt, ids_k, ws=wsk), max(3, args.steps // 2))
+        sweep.append({"samples": k, "tokens": nt, "tokens_per_s": nt / sec_k, "workspace_bytes": need})
     # what the chip sustains on this machine: register-resident MFMA loop and a plain 1 GiB copy (references beside
     # the published peaks)
     sink = torch.zeros(512 * 512, dtype=torch.float32, device=dev)
@@ -203,6 +214,7 @@ def main():
         "mfma_frac_teacher_fwd": fl["teacher"] / sec_teacher / 1e12 / PEAK_BF16_TFLOPS,
         "mfma_frac_student_fwd_bwd_kd": (fl["student"] + fl["kd"]) / sec_student / 1e12 / PEAK_BF16_TFLOPS,
         "loss": loss, "logits_to_hidden_ratio": kd.vocab / kd.h_teacher,
+        "teacher_microbatch_sweep": sweep,
         "measured_references": {"mfma_register_loop_tflops": probe_tflops, "copy_1gib_read_plus_write_gbs": copy_gbs},
         "roofline": {"kernel": "gemm_bf16_fast_kernel (A[M,K] B[N,K]^T, all forward linears and lm_head chunks)",
                      "bound": "mfma", "achieved": achieved, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
