@@ -35,6 +35,18 @@ def model_flops(work):
                 kd=2.0 * n * kd.vocab * (kd.h_teacher + kd.h_student) + 4.0 * n * kd.vocab * kd.h_student)
 
 
+def _tensors(tree):
+    """All tensors of a nested dict / list of weights."""
+    if isinstance(tree, dict):
+        for v in tree.values():
+            yield from _tensors(v)
+    elif isinstance(tree, (list, tuple)):
+        for v in tree:
+            yield from _tensors(v)
+    elif tree is not None and hasattr(tree, "numel"):
+        yield tree
+
+
 def describe(c):
     return f"{c.n_layers}L d{c.d_model} {c.n_q_heads}/{c.n_kv_heads} heads hd{c.head_dim} F{c.d_ffn}"
 
@@ -169,6 +181,14 @@ def main():
         wsk = B.workspace(need, dev, "sweep")
         sec_k, _ = timed(lambda: B.section_forward(t_cfg, tw, bt, ids_k, ws=wsk), max(3, args.steps // 2))
         sweep.append({"samples": k, "tokens": nt, "tokens_per_s": nt / sec_k, "workspace_bytes": need})
+    # the student's AdamW update over all its parameters (outside the timed step: the metric is the KD step)
+    n_par = sum(t.numel() for t in _tensors(sw)) + ws.numel()
+    n_par -= n_par % 4
+    st = [torch.zeros(n_par, dtype=torch.float32, device=dev) for _ in range(4)]
+    w_model = torch.empty(n_par, dtype=dt, device=dev)
+    sec_opt, _ = timed(lambda: B.adamw_step(st[0], st[1], st[2], st[3], w_model, 1, lr=1e-4, weight_decay=0.1), 5)
+    adamw = {"parameters": n_par, "ms": 1e3 * sec_opt, "GB/s": n_par * 30.0 / sec_opt / 1e9}
+    del st, w_model
     # what the chip sustains on this machine: register-resident MFMA loop and a plain 1 GiB copy (references beside
     # the published peaks)
     sink = torch.zeros(512 * 512, dtype=torch.float32, device=dev)
@@ -214,7 +234,7 @@ def main():
         "mfma_frac_teacher_fwd": fl["teacher"] / sec_teacher / 1e12 / PEAK_BF16_TFLOPS,
         "mfma_frac_student_fwd_bwd_kd": (fl["student"] + fl["kd"]) / sec_student / 1e12 / PEAK_BF16_TFLOPS,
         "loss": loss, "logits_to_hidden_ratio": kd.vocab / kd.h_teacher,
-        "teacher_microbatch_sweep": sweep,
+        "teacher_microbatch_sweep": sweep, "student_adamw_step": adamw,
         "measured_references": {"mfma_register_loop_tflops": probe_tflops, "copy_1gib_read_plus_write_gbs": copy_gbs},
         "roofline": {"kernel": "gemm_bf16_fast_kernel (A[M,K] B[N,K]^T, all forward linears and lm_head chunks)",
                      "bound": "mfma", "achieved": achieved, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",

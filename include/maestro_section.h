@@ -152,6 +152,22 @@ ms_status ms_kd_loss_forward_backward(const ms_kd_config *kd, int32_t n_tokens,
                                       void *d_h_student, void *d_w_student,
                                       void *workspace_dev, size_t workspace_bytes, void *stream);
 
+/* The student's parameter update (Sec. 2.2: only the student runs optimizer-driven parameter updates; the
+ * paper names no optimizer, AdamW is the reading taken).  One fused pass over n elements, all device memory:
+ *   g = grad_scale * grad;  m = beta1 m + (1 - beta1) g;  v = beta2 v + (1 - beta2) g^2
+ *   master = master (1 - lr wd) - lr (m / (1 - beta1^step)) / (sqrt(v / (1 - beta2^step)) + eps)
+ *   weight = round(master) in the section's storage type (MS_BF16 or MS_F32)
+ * grad, master, m, v: fp32 [n], 16-byte aligned, updated in place (grad is read only unless zero_grad != 0,
+ * which clears it for the next accumulation); weight: [n] of `dtype` (may be NULL).  step counts from 1.
+ * Arithmetic in fp32. */
+typedef struct {
+    float lr, beta1, beta2, eps, weight_decay, grad_scale;
+    int32_t step;
+    int32_t zero_grad;
+} ms_adamw_config;
+ms_status ms_adamw_step(const ms_adamw_config *cfg, int32_t dtype, int64_t n, float *grad, float *master,
+                        float *m, float *v, void *weight, void *stream);
+
 /* Wavefront sample scheduling (Sec. 3.4, Algorithm 1); host code, all pointers are host memory.
  * tuples[n_samples][6] = (t_f_bc, t_f_c, t_f_ac, t_b_bc, t_b_c, t_b_ac): forward time before / within /
  * after the critical section, then backward time before (sections behind the critical one in forward

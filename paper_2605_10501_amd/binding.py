@@ -217,6 +217,20 @@ def pack_microbatches(lengths, token_budget, policy=0):
     return [order[i] for i in range(offs_l[-1])], offs_l, out
 
 
+class _AdamWCfg(C.Structure):
+    _fields_ = [("lr", C.c_float), ("beta1", C.c_float), ("beta2", C.c_float), ("eps", C.c_float),
+                ("weight_decay", C.c_float), ("grad_scale", C.c_float), ("step", C.c_int32), ("zero_grad", C.c_int32)]
+
+
+def adamw_step(grad, master, m, v, weight, step, lr, beta1=0.9, beta2=0.95, eps=1e-8, weight_decay=0.0, grad_scale=1.0,
+               zero_grad=False):
+    """In-place AdamW update of fp32 master / m / v from fp32 grad; `weight` (bf16 or fp32, or None) gets round(master)."""
+    cfg = _AdamWCfg(lr, beta1, beta2, eps, weight_decay, grad_scale, step, int(zero_grad))
+    dt = MS_F32 if weight is None else _dt(weight.dtype)
+    _check(lib().ms_adamw_step(C.byref(cfg), dt, C.c_int64(master.numel()), _p(grad), _p(master), _p(m), _p(v), _p(weight),
+                               _stream()))
+
+
 def schedule_samples(tuples, interleave=True):
     """tuples: n x 6 times (Sec. 3.4).  Returns (order, makespan)."""
     n = len(tuples)

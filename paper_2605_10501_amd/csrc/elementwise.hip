@@ -668,3 +668,61 @@ ms_status launch_convert_from_f32(int dtype, const float *src, void *dst, long n
     MS_LAUNCH_CHECK();
     return MS_OK;
 }
+
+// ------------------------------------------------------------------ AdamW (the student's parameter update)
+// 4 elements per thread: 16-byte loads and stores of the four fp32 streams, 8 bytes of bf16 weights.
+namespace {
+template <class T>
+__global__ __launch_bounds__(256) void adamw_kernel(long n4, float *__restrict__ grad, float *__restrict__ master,
+                                                     float *__restrict__ m, float *__restrict__ v, T *__restrict__ w,
+                                                     float lr, float b1, float b2, float eps, float decay, float gscale,
+                                                     float inv_c1, float inv_c2, int zero_grad) {
+    const long stride = (long)gridDim.x * 256;
+    for (long i = (long)blockIdx.x * 256 + threadIdx.x; i < n4; i += stride) {
+        const float4 g4 = ((const float4 *)grad)[i], w4 = ((const float4 *)master)[i];
+        const float4 m4 = ((const float4 *)m)[i], v4 = ((const float4 *)v)[i];
+        const float g[4] = {g4.x, g4.y, g4.z, g4.w};
+        float ww[4] = {w4.x, w4.y, w4.z, w4.w}, mm[4] = {m4.x, m4.y, m4.z, m4.w}, vv[4] = {v4.x, v4.y, v4.z, v4.w};
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            const float ge = gscale * g[e];
+            mm[e] = b1 * mm[e] + (1.f - b1) * ge;
+            vv[e] = b2 * vv[e] + (1.f - b2) * ge * ge;
+            ww[e] = ww[e] * decay - lr * (mm[e] * inv_c1) / (sqrtf(vv[e] * inv_c2) + eps);
+        }
+        ((float4 *)master)[i] = make_float4(ww[0], ww[1], ww[2], ww[3]);
+        ((float4 *)m)[i] = make_float4(mm[0], mm[1], mm[2], mm[3]);
+        ((float4 *)v)[i] = make_float4(vv[0], vv[1], vv[2], vv[3]);
+        if (zero_grad) ((float4 *)grad)[i] = make_float4(0.f, 0.f, 0.f, 0.f);
+        if (w) {
+#pragma unroll
+            for (int e = 0; e < 4; ++e) w[4 * i + e] = from_f32<T>(ww[e]);
+        }
+    }
+}
+}  // namespace
+
+extern "C" ms_status ms_adamw_step(const ms_adamw_config *cfg, int32_t dtype, int64_t n, float *grad, float *master,
+                                   float *m, float *v, void *weight, void *stream) {
+    if (!cfg || n < 0) return ms_fail(MS_ERR_INVALID_ARG, "adamw: null config or negative size");
+    if (n == 0) return MS_OK;
+    if (!grad || !master || !m || !v) return ms_fail(MS_ERR_INVALID_ARG, "adamw: null pointer");
+    if (dtype != MS_BF16 && dtype != MS_F32) return ms_fail(MS_ERR_INVALID_ARG, "adamw: bad dtype");
+    if (cfg->step < 1 || !(cfg->beta1 >= 0.f && cfg->beta1 < 1.f) || !(cfg->beta2 >= 0.f && cfg->beta2 < 1.f) || !(cfg->eps >= 0.f) ||
+        !(cfg->lr >= 0.f) || !(cfg->weight_decay >= 0.f))
+        return ms_fail(MS_ERR_INVALID_ARG, "adamw: step must be >= 1, betas in [0, 1), lr, eps and weight decay >= 0");
+    if (n % 4 || !aligned16(grad) || !aligned16(master) || !aligned16(m) || !aligned16(v) || (weight && ((uintptr_t)weight & 7)))
+        return ms_fail(MS_ERR_UNSUPPORTED, "adamw: n must be a multiple of 4 and the arrays 16-byte aligned");
+    // bias corrections in double on the host: 1 - beta^step loses digits in fp32 for small steps
+    const float inv_c1 = (float)(1.0 / (1.0 - pow((double)cfg->beta1, (double)cfg->step)));
+    const float inv_c2 = (float)(1.0 / (1.0 - pow((double)cfg->beta2, (double)cfg->step)));
+    const float decay = 1.f - cfg->lr * cfg->weight_decay;
+    const long n4 = n / 4;
+    const int grid = ms_cdiv(n4, 256) > 16384 ? 16384 : (int)ms_cdiv(n4, 256);
+    hipStream_t s = (hipStream_t)stream;
+    ProfScope ps(11, (double)n * (4 * 7 + (weight ? (dtype == MS_BF16 ? 2 : 4) : 0) + (cfg->zero_grad ? 4 : 0)), s);
+    if (dtype == MS_BF16) adamw_kernel<bf16_t><<<grid, 256, 0, s>>>(n4, grad, master, m, v, (bf16_t *)weight, cfg->lr, cfg->beta1, cfg->beta2, cfg->eps, decay, cfg->grad_scale, inv_c1, inv_c2, cfg->zero_grad);
+    else adamw_kernel<float><<<grid, 256, 0, s>>>(n4, grad, master, m, v, (float *)weight, cfg->lr, cfg->beta1, cfg->beta2, cfg->eps, decay, cfg->grad_scale, inv_c1, inv_c2, cfg->zero_grad);
+    MS_LAUNCH_CHECK();
+    return MS_OK;
+}

@@ -212,3 +212,28 @@ def test_mfma_probe_counts_what_it_claims():
     B.k_mfma_probe(4, 10, sink)
     torch.cuda.synchronize()
     assert torch.all(sink == 480.0)
+
+
+@pytest.mark.parametrize("wdtype", [torch.bfloat16, torch.float32])
+def test_adamw_step_matches_oracle(wdtype):
+    from oracle.optimizer import adamw_step
+    from oracle import round_f32
+    n = 3 * 1024 * 256 + 516                                  # several grid strides and a ragged tail
+    w0 = dev("adam.w", (n,), torch.float32, 0.05)
+    master, m, v = w0.clone(), torch.zeros_like(w0), torch.zeros_like(w0)
+    weight = torch.empty(n, dtype=wdtype, device="cuda")
+    rw, rm, rv = f64(w0), np.zeros(n), np.zeros(n)
+    hp = dict(lr=3e-3, beta1=0.9, beta2=0.95, eps=1e-8, weight_decay=0.1, grad_scale=0.5)
+    for step in range(1, 4):
+        g = dev(f"adam.g{step}", (n,), torch.float32, 0.02 * step)
+        g_ref = f64(g)
+        B.adamw_step(g, master, m, v, weight, step, zero_grad=(step == 3), **hp)
+        rw, rm, rv, _ = adamw_step(rw, rm, rv, g_ref, step, rnd_state=round_f32, **hp)
+        assert_parity(m, rm, 1e-5, f"m step {step}")
+        assert_parity(v, rv, 1e-5, f"v step {step}")
+        assert_parity(master, rw, 1e-5, f"master step {step}")
+        # the model weights are exactly the rounded master weights
+        assert torch.equal(weight, master.to(wdtype))
+        assert (float(g.abs().max()) == 0.0) == (step == 3)   # cleared only when asked
+    with pytest.raises(RuntimeError):
+        B.adamw_step(g, master, m, v, weight, 0, lr=1e-3)     # steps count from 1
