@@ -152,6 +152,36 @@ ms_status ms_kd_loss_forward_backward(const ms_kd_config *kd, int32_t n_tokens,
                                       void *d_h_student, void *d_w_student,
                                       void *workspace_dev, size_t workspace_bytes, void *stream);
 
+/* Vision -> language hand-off (Sec. 2.1 and Sec. 4.1: the encoder's visual tokens are down-sampled 4:1 along the
+ * sequence and joined with the text tokens to form the LLM's input; the operator itself is a reading: patch
+ * merger + MLP projector).  Group g = visual tokens merge*g .. merge*g + merge-1 of the packed encoder output
+ * (each sample's visual length must be a multiple of `merge`, so groups never straddle samples):
+ *   cat[g]  = concat of the group's rows                      [merge * d_vit]   (no copy: adjacent rows)
+ *   out[g]  = W2 gelu(W1 cat[g] + b1) + b2                    [d_llm]           (exact-erf GELU)
+ *   x_llm[positions[g], :] = out[g]                           the LLM's packed embedding stream [n_llm_tokens, d_llm]
+ * Text rows of x_llm are the caller's (embedding gather).  positions_dev: device int32 [n_groups], distinct;
+ * a position outside [0, n_llm_tokens) is skipped (forward) and contributes a zero gradient (backward).
+ * ms_merger_backward: d_x_llm [n_llm_tokens, d_llm] -> d_h_vit [merge * n_groups, d_vit] (overwritten) and
+ * grads (fp32, same shapes as the weights, accumulated).  It reads the activations that ms_merger_forward left
+ * in the workspace for the same n_groups: the workspace must not be touched in between.
+ * w1 [d_hidden, merge * d_vit], b1 [d_hidden], w2 [d_llm, d_hidden], b2 [d_llm] in the storage type; all
+ * widths multiples of 8.  n_groups == 0 (text-only batch) returns MS_OK and launches nothing. */
+typedef struct {
+    int32_t dtype;      /* ms_dtype */
+    int32_t d_vit, merge, d_hidden, d_llm;
+} ms_merger_config;
+typedef struct {
+    const void *w1, *b1, *w2, *b2;
+} ms_merger_ptrs;
+size_t ms_merger_workspace_bytes(const ms_merger_config *cfg, int32_t max_groups);
+ms_status ms_merger_forward(const ms_merger_config *cfg, const ms_merger_ptrs *weights, int32_t n_groups,
+                            const void *h_vit, const int32_t *positions_dev, int32_t n_llm_tokens,
+                            void *x_llm, void *workspace_dev, size_t workspace_bytes, void *stream);
+ms_status ms_merger_backward(const ms_merger_config *cfg, const ms_merger_ptrs *weights,
+                             const ms_merger_ptrs *grads, int32_t n_groups, const void *h_vit,
+                             const int32_t *positions_dev, int32_t n_llm_tokens, const void *d_x_llm,
+                             void *d_h_vit, void *workspace_dev, size_t workspace_bytes, void *stream);
+
 /* The student's parameter update (Sec. 2.2: only the student runs optimizer-driven parameter updates; the
  * paper names no optimizer, AdamW is the reading taken).  One fused pass over n elements, all device memory:
  *   g = grad_scale * grad;  m = beta1 m + (1 - beta1) g;  v = beta2 v + (1 - beta2) g^2

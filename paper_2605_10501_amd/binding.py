@@ -217,6 +217,45 @@ def pack_microbatches(lengths, token_budget, policy=0):
     return [order[i] for i in range(offs_l[-1])], offs_l, out
 
 
+class _MergerCfg(C.Structure):
+    _fields_ = [("dtype", C.c_int32), ("d_vit", C.c_int32), ("merge", C.c_int32), ("d_hidden", C.c_int32), ("d_llm", C.c_int32)]
+
+
+class _MergerPtrs(C.Structure):
+    _fields_ = [(k, C.c_void_p) for k in ("w1", "b1", "w2", "b2")]
+
+
+def _merger_c(w, merge):
+    dh, din = w["w1"].shape
+    return _MergerCfg(_dt(w["w1"].dtype), din // merge, merge, dh, w["w2"].shape[0])
+
+
+def _merger_ptrs(t):
+    return _MergerPtrs(*[_p(t[k]) for k in ("w1", "b1", "w2", "b2")])
+
+
+def merger_workspace_bytes(w, n_groups, merge=4):
+    c = _merger_c(w, merge)
+    lib().ms_merger_workspace_bytes.restype = C.c_size_t
+    return lib().ms_merger_workspace_bytes(C.byref(c), n_groups)
+
+
+def merger_forward(w, h_vit, positions, x_llm, ws, merge=4):
+    """Writes the projected visual rows into x_llm (in place) at `positions` (int32 device tensor)."""
+    c, pw = _merger_c(w, merge), _merger_ptrs(w)
+    _check(lib().ms_merger_forward(C.byref(c), C.byref(pw), positions.numel(), _p(h_vit), _p(positions), x_llm.shape[0], _p(x_llm),
+                                   _p(ws), C.c_size_t(ws.numel()), _stream()))
+
+
+def merger_backward(w, grads, h_vit, positions, d_x_llm, ws, merge=4):
+    """Returns d_h_vit; `grads` (fp32 dict like w) is accumulated in place.  `ws` must be the forward call's workspace."""
+    c, pw, pg = _merger_c(w, merge), _merger_ptrs(w), _merger_ptrs(grads)
+    d_h = torch.empty_like(h_vit)
+    _check(lib().ms_merger_backward(C.byref(c), C.byref(pw), C.byref(pg), positions.numel(), _p(h_vit), _p(positions),
+                                    d_x_llm.shape[0], _p(d_x_llm), _p(d_h), _p(ws), C.c_size_t(ws.numel()), _stream()))
+    return d_h
+
+
 class _AdamWCfg(C.Structure):
     _fields_ = [("lr", C.c_float), ("beta1", C.c_float), ("beta2", C.c_float), ("eps", C.c_float),
                 ("weight_decay", C.c_float), ("grad_scale", C.c_float), ("step", C.c_int32), ("zero_grad", C.c_int32)]
