@@ -93,6 +93,8 @@ def main():
     ap.add_argument("--workload", default="c2")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample-tokens", type=int, default=2048)
+    ap.add_argument("--step-only", action="store_true",
+                    help="skip the side measurements (teacher sweep, AdamW, references): for profiler runs of the step")
     ap.add_argument("--copy-calibration", type=int, default=0, metavar="MIB",
                     help="also run the library's copy kernel 3x on MIB MiB (reference dispatch for counter runs)")
     args = ap.parse_args()
@@ -159,8 +161,10 @@ def main():
     sec_teacher, _ = timed(teacher, args.steps)
     sec_student, _ = timed(student, args.steps)
     # the KD head alone (both lm_heads, loss, gradients to the student hidden states and lm_head) on this batch
-    h_s = wl.normal(0, "bench.h_s", (n, kd.h_student), 1.0, 0.0, dt, dev)
-    sec_kd, _ = timed(lambda: B.kd_loss_forward_backward(kd, wt, ws, h_t, h_s, d_w_student=d_ws), args.steps)
+    sec_kd = float("nan")
+    if not args.step_only:
+        h_s = wl.normal(0, "bench.h_s", (n, kd.h_student), 1.0, 0.0, dt, dev)
+        sec_kd, _ = timed(lambda: B.kd_loss_forward_backward(kd, wt, ws, h_t, h_s, d_w_student=d_ws), args.steps)
 
     # per-kernel durations from HIP events on the launch stream (separate, untimed-for-value steps)
     B.profile_enable(1)
@@ -170,35 +174,37 @@ def main():
     torch.cuda.synchronize()
     prof = B.profile_read()
     B.profile_enable(0)
-    # teacher micro-batch sweep (Sec. 4.2: a forward-only teacher is under-utilised by small micro-batches):
-    # forward rate and workspace of the teacher section at 1, 2, 4, 8 packed samples of 4096 tokens
-    sweep = []
-    for k in (1, 2, 4, 8):
-        nt = 4096 * k
-        bt = B.Batch([4096 * i for i in range(k + 1)])
-        ids_k = wl.randint(0, "sweep.ids", nt, 0, t_cfg.vocab, dev)
-        need = B.section_workspace_bytes(t_cfg, nt, 4096, False)
-        wsk = B.workspace(need, dev, "sweep")
-        sec_k, _ = timed(lambda: B.section_forward(t_cfg, tw, bt, ids_k, ws=wsk), max(3, args.steps // 2))
-        sweep.append({"samples": k, "tokens": nt, "tokens_per_s": nt / sec_k, "workspace_bytes": need})
-    # the student's AdamW update over all its parameters (outside the timed step: the metric is the KD step)
-    n_par = sum(t.numel() for t in _tensors(sw)) + ws.numel()
-    n_par -= n_par % 4
-    st = [torch.zeros(n_par, dtype=torch.float32, device=dev) for _ in range(4)]
-    w_model = torch.empty(n_par, dtype=dt, device=dev)
-    sec_opt, _ = timed(lambda: B.adamw_step(st[0], st[1], st[2], st[3], w_model, 1, lr=1e-4, weight_decay=0.1), 5)
-    adamw = {"parameters": n_par, "ms": 1e3 * sec_opt, "GB/s": n_par * 30.0 / sec_opt / 1e9}
-    del st, w_model
-    # what the chip sustains on this machine: register-resident MFMA loop and a plain 1 GiB copy (references beside
-    # the published peaks)
-    sink = torch.zeros(512 * 512, dtype=torch.float32, device=dev)
-    sec_probe, _ = timed(lambda: B.k_mfma_probe(512, 10000, sink), 3)
-    probe_tflops = 512 * 8 * 10000 * 8 * 32768 / sec_probe / 1e12
-    src = torch.ones(1 << 30, dtype=torch.uint8, device=dev)
-    dst = torch.empty_like(src)
-    sec_copy, _ = timed(lambda: B.k_copy(src, dst), 3)
-    copy_gbs = 2.0 * (1 << 30) / sec_copy / 1e9
-    del src, dst, sink
+    sweep, adamw, probe_tflops, copy_gbs = [], None, None, None
+    if not args.step_only:
+        # teacher micro-batch sweep (Sec. 4.2: a forward-only teacher is under-utilised by small micro-batches):
+        # forward rate and workspace of the teacher section at 1, 2, 4, 8 packed samples of 4096 tokens
+        sweep = []
+        for k in (1, 2, 4, 8):
+            nt = 4096 * k
+            bt = B.Batch([4096 * i for i in range(k + 1)])
+            ids_k = wl.randint(0, "sweep.ids", nt, 0, t_cfg.vocab, dev)
+            need = B.section_workspace_bytes(t_cfg, nt, 4096, False)
+            wsk = B.workspace(need, dev, "sweep")
+            sec_k, _ = timed(lambda: B.section_forward(t_cfg, tw, bt, ids_k, ws=wsk), max(3, args.steps // 2))
+            sweep.append({"samples": k, "tokens": nt, "tokens_per_s": nt / sec_k, "workspace_bytes": need})
+        # the student's AdamW update over all its parameters (outside the timed step: the metric is the KD step)
+        n_par = sum(t.numel() for t in _tensors(sw)) + ws.numel()
+        n_par -= n_par % 4
+        st = [torch.zeros(n_par, dtype=torch.float32, device=dev) for _ in range(4)]
+        w_model = torch.empty(n_par, dtype=dt, device=dev)
+        sec_opt, _ = timed(lambda: B.adamw_step(st[0], st[1], st[2], st[3], w_model, 1, lr=1e-4, weight_decay=0.1), 5)
+        adamw = {"parameters": n_par, "ms": 1e3 * sec_opt, "GB/s": n_par * 30.0 / sec_opt / 1e9}
+        del st, w_model
+        # what the chip sustains on this machine: register-resident MFMA loop and a plain 1 GiB copy (references beside
+        # the published peaks)
+        sink = torch.zeros(512 * 512, dtype=torch.float32, device=dev)
+        sec_probe, _ = timed(lambda: B.k_mfma_probe(512, 10000, sink), 3)
+        probe_tflops = 512 * 8 * 10000 * 8 * 32768 / sec_probe / 1e12
+        src = torch.ones(1 << 30, dtype=torch.uint8, device=dev)
+        dst = torch.empty_like(src)
+        sec_copy, _ = timed(lambda: B.k_copy(src, dst), 3)
+        copy_gbs = 2.0 * (1 << 30) / sec_copy / 1e9
+        del src, dst, sink
     fl = model_flops(work)
     g_n, g_ms, g_work = prof["gemm_nt"]
     gt_n, gt_ms, gt_work = prof["gemm_t"]
@@ -228,14 +234,16 @@ def main():
                                f"teacher {describe(t_cfg)}, student {describe(s_cfg)}, vocab {kd.vocab}, "
                                f"T={kd.temperature:g}, chunk {kd.chunk}"},
         "teacher_fwd_tokens_per_s": n / sec_teacher, "student_fwd_bwd_kd_tokens_per_s": n / sec_student,
-        "kd_loss_fwd_bwd_tokens_per_s": n / sec_kd, "mfma_frac_kd_loss": fl["kd"] / sec_kd / 1e12 / PEAK_BF16_TFLOPS,
+        "kd_loss_fwd_bwd_tokens_per_s": None if args.step_only else n / sec_kd,
+        "mfma_frac_kd_loss": None if args.step_only else fl["kd"] / sec_kd / 1e12 / PEAK_BF16_TFLOPS,
         "model_tflop_per_step": total_flops / 1e12,
         "mfma_frac_whole_step": total_flops / sec_step / 1e12 / PEAK_BF16_TFLOPS,
         "mfma_frac_teacher_fwd": fl["teacher"] / sec_teacher / 1e12 / PEAK_BF16_TFLOPS,
         "mfma_frac_student_fwd_bwd_kd": (fl["student"] + fl["kd"]) / sec_student / 1e12 / PEAK_BF16_TFLOPS,
         "loss": loss, "logits_to_hidden_ratio": kd.vocab / kd.h_teacher,
         "teacher_microbatch_sweep": sweep, "student_adamw_step": adamw,
-        "measured_references": {"mfma_register_loop_tflops": probe_tflops, "copy_1gib_read_plus_write_gbs": copy_gbs},
+        "measured_references": None if args.step_only else {"mfma_register_loop_tflops": probe_tflops,
+                                                             "copy_1gib_read_plus_write_gbs": copy_gbs},
         "roofline": {"kernel": "gemm_bf16_fast_kernel (A[M,K] B[N,K]^T, all forward linears and lm_head chunks)",
                      "bound": "mfma", "achieved": achieved, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
                      "frac": achieved / PEAK_BF16_TFLOPS, "traffic": traffic,
