@@ -204,7 +204,8 @@ ms_status ms_adamw_step(const ms_adamw_config *cfg, int32_t dtype, int64_t n, fl
  * order) / within / after (sections in front of it) the critical section; non-negative, any unit.
  * ms_schedule_samples: stable sort by t_f_bc, then each remaining sample is inserted at the position
  * (lowest on ties; makespans within 1e-9 relative are ties) that gives the least simulated makespan; order_out[n_samples] receives sample indices
- * in execution order, *makespan_out (optional) the simulated makespan.  O(n^3) time.
+ * in execution order, *makespan_out (optional) the simulated makespan.  O(n^2) time for interleave != 0
+ * (insertions are evaluated through (max, +) prefix states and suffix products), O(n^3) otherwise.
  * ms_schedule_makespan: makespan of a given order (a permutation of 0..n-1, else MS_ERR_INVALID_ARG) and
  * (optional) the time the critical section spends idle before its last job ends.
  * Timeline model: three serial servers (sections in front of the critical one, the critical section, the
