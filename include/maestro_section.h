@@ -106,6 +106,10 @@ typedef struct {
     float loss_scale;              /* loss = loss_scale * sum_tokens KL_token        */
     const void *w_teacher_dev;     /* [vocab, h_teacher]                             */
     const void *w_student_dev;     /* [vocab, h_student]                             */
+    int32_t token_block;           /* 0: chunk + recompute, at most [N, chunk] logits per model.  > 0 (multiple of */
+                                   /* 8): variant for large HBM: tokens go in blocks of this many and a block's     */
+                                   /* teacher logits ([token_block, vocab] fp32, independent of N) stay in the      */
+                                   /* workspace between the two passes instead of being recomputed                  */
 } ms_kd_config;
 
 /* Bytes of device workspace the calls below need for up to max_tokens packed tokens

@@ -39,7 +39,7 @@ class BatchC(C.Structure):
 class KDConfigC(C.Structure):
     _fields_ = [("vocab", C.c_int32), ("h_teacher", C.c_int32), ("h_student", C.c_int32), ("chunk", C.c_int32),
                 ("dtype", C.c_int32), ("temperature", C.c_float), ("loss_scale", C.c_float),
-                ("w_teacher_dev", C.c_void_p), ("w_student_dev", C.c_void_p)]
+                ("w_teacher_dev", C.c_void_p), ("w_student_dev", C.c_void_p), ("token_block", C.c_int32)]
 
 
 _lib = None
@@ -119,7 +119,7 @@ def _ptrs_c(cfg, w):
 
 def _kd_c(kd, w_teacher, w_student, loss_scale):
     return KDConfigC(kd.vocab, kd.h_teacher, kd.h_student, kd.chunk, _dt(kd.dtype), kd.temperature, loss_scale,
-                     w_teacher.data_ptr(), w_student.data_ptr())
+                     w_teacher.data_ptr(), w_student.data_ptr(), getattr(kd, "token_block", 0))
 
 
 def zero_grads(weights):
@@ -148,7 +148,8 @@ def section_workspace_bytes(cfg, max_tokens, max_seqlen, need_backward):
 
 
 def kd_workspace_bytes(kd, max_tokens):
-    c = KDConfigC(kd.vocab, kd.h_teacher, kd.h_student, kd.chunk, _dt(kd.dtype), kd.temperature, 1.0, None, None)
+    c = KDConfigC(kd.vocab, kd.h_teacher, kd.h_student, kd.chunk, _dt(kd.dtype), kd.temperature, 1.0, None, None,
+                  getattr(kd, "token_block", 0))
     return lib().ms_kd_workspace_bytes(C.byref(c), max_tokens)
 
 

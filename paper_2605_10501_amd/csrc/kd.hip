@@ -14,7 +14,7 @@
 
 namespace {
 
-constexpr int kStat = 8;  // floats per token: m_t, s_t, m_s, s_s, A, unused, lse_t, lse_s
+constexpr int kStat = 8;  // floats per token: m_t, s_t, m_s, s_s, A, KL, lse_t, lse_s
 
 __device__ __forceinline__ float block_max(float v, float *sm) {
     v = wave_max(v);
@@ -85,21 +85,26 @@ __global__ __launch_bounds__(256) void kd_stats_kernel(const float *__restrict__
     }
 }
 
-// single workgroup: per-token KL, log-sum-exps for pass 2, and the scalar loss (fixed summation order)
-__global__ __launch_bounds__(1024) void kd_finalize_kernel(float *__restrict__ stats, int n, float loss_scale,
-                                                            float *__restrict__ kl_tok, float *__restrict__ loss) {
+// per token: log-sum-exps for pass 2 (slots 6, 7 of its statistics) and its KL term (slot 5)
+__global__ __launch_bounds__(256) void kd_token_kernel(float *__restrict__ stats, int n, float *__restrict__ kl_tok) {
+    const int t = blockIdx.x * 256 + threadIdx.x;
+    if (t >= n) return;
+    float *st = stats + (long)t * kStat;
+    const float lse_t = st[0] + __logf(st[1]);
+    const float lse_s = st[2] + __logf(st[3]);
+    const float kl = st[4] / st[1] - lse_t + lse_s;
+    st[5] = kl;
+    st[6] = lse_t;
+    st[7] = lse_s;
+    if (kl_tok) kl_tok[t] = kl;
+}
+
+// single workgroup: the scalar loss from the per-token KL terms (fixed summation order)
+__global__ __launch_bounds__(1024) void kd_loss_kernel(const float *__restrict__ stats, int n, float loss_scale,
+                                                        float *__restrict__ loss) {
     __shared__ float sm[16];
     float acc = 0.f;
-    for (int t = threadIdx.x; t < n; t += 1024) {
-        float *st = stats + (long)t * kStat;
-        const float lse_t = st[0] + __logf(st[1]);
-        const float lse_s = st[2] + __logf(st[3]);
-        const float kl = st[4] / st[1] - lse_t + lse_s;
-        st[6] = lse_t;
-        st[7] = lse_s;
-        if (kl_tok) kl_tok[t] = kl;
-        acc += kl;
-    }
+    for (int t = threadIdx.x; t < n; t += 1024) acc += stats[(long)t * kStat + 5];
     acc = block_sum(acc, sm);
     if (threadIdx.x == 0) *loss = loss_scale * acc;
 }
@@ -163,13 +168,21 @@ struct KdPlan {
     float *zt, *zs, *stats, *dhs;
     void *dz;
     size_t bytes;
+    int tb;            // tokens per block
+    bool keep;         // teacher logits of a block are kept across the two passes (one [tb, chunk] slab per chunk)
 };
 
+// token_block > 0: the tokens are processed in blocks of that many, and the teacher logits of the current block
+// stay in the workspace between the statistics pass and the gradient pass (no teacher recompute); the cache
+// is [n_chunks][token_block][chunk] fp32, independent of the number of tokens.
 KdPlan kd_plan(const ms_kd_config *kd, int n, void *ws) {
     Arena a(ws);
     KdPlan p;
-    const size_t nc = (size_t)n * kd->chunk;
-    p.zt = a.take<float>(nc * 4);
+    p.keep = kd->token_block > 0;
+    p.tb = p.keep && kd->token_block < n ? kd->token_block : n;
+    const size_t nc = (size_t)p.tb * kd->chunk;
+    const size_t nchunks = p.keep ? (size_t)ms_cdiv(kd->vocab, kd->chunk) : 1;
+    p.zt = a.take<float>(nchunks * nc * 4);
     p.zs = a.take<float>(nc * 4);
     p.stats = a.take<float>((size_t)n * kStat * 4);
     p.dz = a.take<void>(nc * ms_dtype_size(kd->dtype));
@@ -187,6 +200,7 @@ ms_status validate_kd(const ms_kd_config *kd, int n_tokens) {
     if (kd->vocab <= 0 || kd->h_teacher <= 0 || kd->h_student <= 0 || kd->chunk <= 0)
         return ms_fail(MS_ERR_SHAPE, "kd: vocab, hidden sizes and chunk must be positive");
     if (!(kd->temperature > 0.f)) return ms_fail(MS_ERR_INVALID_ARG, "kd: temperature must be positive");
+    if (kd->token_block < 0 || kd->token_block % 8) return ms_fail(MS_ERR_INVALID_ARG, "kd: token_block must be 0 or a positive multiple of 8");
     if (kd->vocab % 8 || kd->chunk % 8 || kd->h_teacher % 8 || kd->h_student % 8)
         return ms_fail(MS_ERR_UNSUPPORTED, "kd: vocab, chunk and hidden sizes must be multiples of 8");
     if (!kd->w_teacher_dev || !kd->w_student_dev) return ms_fail(MS_ERR_INVALID_ARG, "kd: null lm_head pointer");
@@ -212,57 +226,67 @@ ms_status kd_forward_backward(const ms_kd_config *kd, int n, const void *h_t, co
     const float inv_t = 1.f / kd->temperature;
     const char *wt = (const char *)kd->w_teacher_dev, *wsd = (const char *)kd->w_student_dev;
     const int passes = (d_h_s || d_w_s) ? 2 : 1;
+    const bool keep = p.keep && passes == 2;
     if (d_h_s) MS_TRY(launch_fill_f32(p.dhs, (long)n * Hs, 0.f, s));
-    // bf16 fast path: the student-logits GEMM consumes its own output (statistics in pass 1, dz in pass 2)
-    // together with the stored teacher logits; the zs buffer then only holds the per-strip partials
-    bool fused = dt == MS_BF16;
-    for (int v0 = 0; v0 < V && fused; v0 += Cv) {
-        const int cw = V - v0 < Cv ? V - v0 : Cv;
-        fused = gemm_kd_epilogue_supported(n, cw, Hs, h_s, Hs, wsd + (size_t)v0 * Hs * es, Hs, p.zt, Cv, p.dz, Cv, 0);
-    }
-    for (int pass = 0; pass < passes; ++pass) {
-        for (int v0 = 0; v0 < V; v0 += Cv) {
+    for (int t0 = 0; t0 < n; t0 += p.tb) {
+        const int nb = n - t0 < p.tb ? n - t0 : p.tb;
+        const char *ht_b = (const char *)h_t + (size_t)t0 * Ht * es, *hs_b = (const char *)h_s + (size_t)t0 * Hs * es;
+        float *stats_b = p.stats + (size_t)t0 * kStat, *dhs_b = p.dhs + (size_t)t0 * Hs;
+        // bf16 fast path: the student-logits GEMM consumes its own output (statistics in pass 1, dz in pass 2)
+        // together with the stored teacher logits; the zs buffer then only holds the per-strip partials
+        bool fused = dt == MS_BF16;
+        for (int v0 = 0; v0 < V && fused; v0 += Cv) {
             const int cw = V - v0 < Cv ? V - v0 : Cv;
-            MS_TRY(ms_k_gemm(dt, 0, 0, n, cw, Ht, 1.f, h_t, Ht, wt + (size_t)v0 * Ht * es, Ht, p.zt, Cv, 1, 0, nullptr, nullptr, 0, 0, 1, s));
-            if (fused) {
-                const int nparts = ms_cdiv(cw, 64);
-                if (pass == 0) {
-                    MS_TRY(gemm_kd_epilogue(2, n, cw, Hs, h_s, Hs, wsd + (size_t)v0 * Hs * es, Hs, p.zt, Cv, nullptr, p.zs, nparts,
-                                            inv_t, 0.f, nullptr, 0, 0, s));
-                    ProfScope ps(9, 32.0 * n * nparts, s);
-                    kd_combine_kernel<<<ms_cdiv(n, 4), 256, 0, s>>>(p.zs, nparts, n, v0 == 0, p.stats);
+            fused = gemm_kd_epilogue_supported(nb, cw, Hs, hs_b, Hs, wsd + (size_t)v0 * Hs * es, Hs, p.zt, Cv, p.dz, Cv, 0);
+        }
+        for (int pass = 0; pass < passes; ++pass) {
+            for (int v0 = 0, ci = 0; v0 < V; v0 += Cv, ++ci) {
+                const int cw = V - v0 < Cv ? V - v0 : Cv;
+                float *zt = keep ? p.zt + (size_t)ci * p.tb * Cv : p.zt;
+                if (pass == 0 || !keep)
+                    MS_TRY(ms_k_gemm(dt, 0, 0, nb, cw, Ht, 1.f, ht_b, Ht, wt + (size_t)v0 * Ht * es, Ht, zt, Cv, 1, 0, nullptr, nullptr, 0, 0, 1, s));
+                if (fused) {
+                    const int nparts = ms_cdiv(cw, 64);
+                    if (pass == 0) {
+                        MS_TRY(gemm_kd_epilogue(2, nb, cw, Hs, hs_b, Hs, wsd + (size_t)v0 * Hs * es, Hs, zt, Cv, nullptr, p.zs, nparts,
+                                                inv_t, 0.f, nullptr, 0, 0, s));
+                        ProfScope ps(9, 32.0 * nb * nparts, s);
+                        kd_combine_kernel<<<ms_cdiv(nb, 4), 256, 0, s>>>(p.zs, nparts, nb, v0 == 0, stats_b);
+                        MS_LAUNCH_CHECK();
+                        continue;
+                    }
+                    MS_TRY(gemm_kd_epilogue(1, nb, cw, Hs, hs_b, Hs, wsd + (size_t)v0 * Hs * es, Hs, zt, Cv, stats_b, nullptr, 0, inv_t,
+                                            kd->loss_scale * inv_t, p.dz, Cv, 0, s));
+                } else {
+                    MS_TRY(ms_k_gemm(dt, 0, 0, nb, cw, Hs, 1.f, hs_b, Hs, wsd + (size_t)v0 * Hs * es, Hs, p.zs, Cv, 1, 0, nullptr, nullptr, 0, 0, 1, s));
+                    if (pass == 0) {
+                        ProfScope ps(9, 8.0 * nb * cw, s);
+                        kd_stats_kernel<<<nb, 256, 0, s>>>(zt, p.zs, Cv, cw, inv_t, v0 == 0, stats_b);
+                        MS_LAUNCH_CHECK();
+                        continue;
+                    }
+                    const float coef = kd->loss_scale * inv_t;
+                    dim3 grid(ms_cdiv(cw, 1024), nb);
+                    {
+                        ProfScope ps(10, (8.0 + es) * nb * cw, s);
+                        if (dt == MS_BF16) kd_dz_kernel<bf16_t><<<grid, 256, 0, s>>>(zt, p.zs, Cv, cw, inv_t, coef, stats_b, (bf16_t *)p.dz);
+                        else kd_dz_kernel<float><<<grid, 256, 0, s>>>(zt, p.zs, Cv, cw, inv_t, coef, stats_b, (float *)p.dz);
+                    }
                     MS_LAUNCH_CHECK();
-                    continue;
                 }
-                MS_TRY(gemm_kd_epilogue(1, n, cw, Hs, h_s, Hs, wsd + (size_t)v0 * Hs * es, Hs, p.zt, Cv, p.stats, nullptr, 0, inv_t,
-                                        kd->loss_scale * inv_t, p.dz, Cv, 0, s));
-            } else {
-                MS_TRY(ms_k_gemm(dt, 0, 0, n, cw, Hs, 1.f, h_s, Hs, wsd + (size_t)v0 * Hs * es, Hs, p.zs, Cv, 1, 0, nullptr, nullptr, 0, 0, 1, s));
-                if (pass == 0) {
-                    ProfScope ps(9, 8.0 * n * cw, s);
-                    kd_stats_kernel<<<n, 256, 0, s>>>(p.zt, p.zs, Cv, cw, inv_t, v0 == 0, p.stats);
-                    MS_LAUNCH_CHECK();
-                    continue;
-                }
-                const float coef = kd->loss_scale * inv_t;
-                dim3 grid(ms_cdiv(cw, 1024), n);
-                {
-                    ProfScope ps(10, (8.0 + es) * n * cw, s);
-                    if (dt == MS_BF16) kd_dz_kernel<bf16_t><<<grid, 256, 0, s>>>(p.zt, p.zs, Cv, cw, inv_t, coef, p.stats, (bf16_t *)p.dz);
-                    else kd_dz_kernel<float><<<grid, 256, 0, s>>>(p.zt, p.zs, Cv, cw, inv_t, coef, p.stats, (float *)p.dz);
-                }
+                if (d_h_s)  // dHs[N, Hs] += dz[N, cw] Ws_c[cw, Hs]
+                    MS_TRY(ms_k_gemm(dt, 0, 1, nb, Hs, cw, 1.f, p.dz, Cv, wsd + (size_t)v0 * Hs * es, Hs, dhs_b, Hs, 1, 1, nullptr, nullptr, 0, 0, 1, s));
+                if (d_w_s)  // dWs_c[cw, Hs] += dz^T[cw, N] Hs[N, Hs]
+                    MS_TRY(ms_k_gemm(dt, 1, 1, cw, Hs, nb, 1.f, p.dz, Cv, hs_b, Hs, (float *)d_w_s + (size_t)v0 * Hs, Hs, 1, 1, nullptr, nullptr, 0, 0, 0, s));
+            }
+            if (pass == 0) {
+                kd_token_kernel<<<ms_cdiv(nb, 256), 256, 0, s>>>(stats_b, nb, kl_tok_dev ? kl_tok_dev + t0 : nullptr);
                 MS_LAUNCH_CHECK();
             }
-            if (d_h_s)  // dHs[N, Hs] += dz[N, cw] Ws_c[cw, Hs]
-                MS_TRY(ms_k_gemm(dt, 0, 1, n, Hs, cw, 1.f, p.dz, Cv, wsd + (size_t)v0 * Hs * es, Hs, p.dhs, Hs, 1, 1, nullptr, nullptr, 0, 0, 1, s));
-            if (d_w_s)  // dWs_c[cw, Hs] += dz^T[cw, N] Hs[N, Hs]
-                MS_TRY(ms_k_gemm(dt, 1, 1, cw, Hs, n, 1.f, p.dz, Cv, h_s, Hs, (float *)d_w_s + (size_t)v0 * Hs, Hs, 1, 1, nullptr, nullptr, 0, 0, 0, s));
-        }
-        if (pass == 0) {
-            kd_finalize_kernel<<<1, 1024, 0, s>>>(p.stats, n, kd->loss_scale, kl_tok_dev, loss_dev);
-            MS_LAUNCH_CHECK();
         }
     }
+    kd_loss_kernel<<<1, 1024, 0, s>>>(p.stats, n, kd->loss_scale, loss_dev);
+    MS_LAUNCH_CHECK();
     if (d_h_s) MS_TRY(launch_convert_from_f32(dt, p.dhs, d_h_s, (long)n * Hs, s));
     return MS_OK;
 }

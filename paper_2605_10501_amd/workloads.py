@@ -121,6 +121,7 @@ class KDConfig:
     temperature: float = 1.0
     chunk: int = 8192
     dtype: str = "bf16"
+    token_block: int = 0         # > 0: keep a token block's teacher logits across the two KD passes (variant)
 
 
 @dataclass

@@ -152,10 +152,13 @@ def test_skipped_section_is_a_noop():
     assert all(float(t.abs().max()) == 0.0 for t in grads["layers"][0].values())
 
 
-@pytest.mark.parametrize("dtype,vocab,chunk,n,ht,hs,T", [
-    ("bf16", 5000, 1024, 700, 512, 256, 2.0), ("bf16", 2048, 2048, 130, 136, 72, 1.0), ("fp32", 1000, 256, 97, 64, 32, 1.5)])
-def test_kd_loss_standalone(dtype, vocab, chunk, n, ht, hs, T):
-    kd = wl.KDConfig(vocab, ht, hs, T, chunk, dtype)
+@pytest.mark.parametrize("dtype,vocab,chunk,n,ht,hs,T,token_block", [
+    ("bf16", 5000, 1024, 700, 512, 256, 2.0, 0), ("bf16", 2048, 2048, 130, 136, 72, 1.0, 0), ("fp32", 1000, 256, 97, 64, 32, 1.5, 0),
+    # the variant that keeps a token block's teacher logits between the passes: three ragged blocks, one block
+    # larger than the batch, and the unfused fp32 path
+    ("bf16", 5000, 1024, 700, 512, 256, 2.0, 256), ("bf16", 5000, 1024, 700, 512, 256, 2.0, 4096), ("fp32", 1000, 256, 97, 64, 32, 1.5, 40)])
+def test_kd_loss_standalone(dtype, vocab, chunk, n, ht, hs, T, token_block):
+    kd = wl.KDConfig(vocab, ht, hs, T, chunk, dtype, token_block)
     dt = torch.bfloat16 if dtype == "bf16" else torch.float32
     rnd = round_bf16 if dtype == "bf16" else identity
     h_t, h_s = wl.normal(3, "ht", (n, ht), 1.0, 0.0, dt, "cuda"), wl.normal(3, "hs", (n, hs), 1.0, 0.0, dt, "cuda")
