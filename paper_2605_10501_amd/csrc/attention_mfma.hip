@@ -416,12 +416,15 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
 
     const bf16_t *vrow = Vs + (wave >> 1) * VS;             // the 64-key row tile holding this wave's keys
     const int vr = (wave & 1) * 32 + lrow;
-    // One pass over the query tiles accumulates dV (WHICH = 0: needs S only) or dK (WHICH = 1: needs S
-    // and dP).  Two passes cost one extra S product per tile but halve the accumulators, which is what
-    // lets two workgroups share a CU.
-    f32x16 acc[D::DB];
+    // One pass over the query tiles accumulates dV (WHICH = 0: needs S only), dK (1: needs S and dP) or both
+    // (2).  With wide heads the two accumulator sets do not fit 256 registers: two passes (0 then 1) cost one
+    // extra S product and a second round of exponentials per tile but halve the accumulators, which is what
+    // lets two workgroups share a CU.  Heads of at most 96 columns fit both sets: one pass.
+    constexpr bool ONE_PASS = D::DB <= 3;
+    f32x16 acc[D::DB], acc2[ONE_PASS ? D::DB : 1];          // acc2: dV when both are accumulated (acc is dK then)
     auto compute = [&](auto which, int it, const bf16_t *qt_, const bf16_t *ot_, const float *f) __attribute__((always_inline)) {
-        constexpr bool DK = decltype(which)::value;
+        constexpr int WHICH = decltype(which)::value;
+        constexpr bool DK = WHICH >= 1, BOTH = WHICH == 2;
         const float *ls = f, *dl = f + 32;
         const int qs = s0 + (qt_first + it % nqt) * BQ;
         if (CAUSAL && qs + BQ - 1 < kw0) return;            // every query of the tile precedes every key of the wave
@@ -443,7 +446,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
         // 16 queries (one MFMA k-step of the second product) at a time, to keep few values live
 #pragma unroll
         for (int t = 0; t < 2; ++t) {
-            float w[8];
+            float w[8], w2[BOTH ? 8 : 1];
 #pragma unroll
             for (int rg = 0; rg < 2; ++rg) {
                 const int qr = 16 * t + 8 * rg + 4 * half;
@@ -463,6 +466,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
                         pe = (kok && qq < s1 && (!CAUSAL || key <= qq)) ? pe : 0.f;
                     }
                     w[r] = DK ? pe * (dp[8 * t + r] - dvv[e]) : pe;
+                    if constexpr (BOTH) w2[r] = pe;
                 }
             }
             const bf16x8 wf = pack8(w);
@@ -470,10 +474,16 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
 #pragma unroll
             for (int db = 0; db < D::DB; ++db)
                 acc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf, rowtile_tr_frag<2048>(bt, 16 * t, db * 32, lane), acc[db], 0, 0, 0);
+            if constexpr (BOTH) {
+                const bf16x8 pf = pack8(w2);
+#pragma unroll
+                for (int db = 0; db < D::DB; ++db)
+                    acc2[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(pf, rowtile_tr_frag<2048>(ot_, 16 * t, db * 32, lane), acc2[db], 0, 0, 0);
+            }
         }
     };
     // accumulators: row = key wave*32 + 8*(r/4) + 4*half + r%4, column d = db*32 + lrow
-    auto store = [&](int col0, float mul) __attribute__((always_inline)) {
+    auto store = [&](const f32x16 *acc, int col0, float mul) __attribute__((always_inline)) {
 #pragma unroll
         for (int db = 0; db < D::DB; ++db) {
             const int d = db * 32 + lrow;
@@ -491,7 +501,10 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
 #pragma unroll
         for (int i = 0; i < D::DB; ++i)
 #pragma unroll
-            for (int r = 0; r < 16; ++r) acc[i][r] = 0.f;
+            for (int r = 0; r < 16; ++r) {
+                acc[i][r] = 0.f;
+                if constexpr (ONE_PASS) acc2[i][r] = 0.f;
+            }
         issue(0, Q0, O0, F0);
         __syncthreads();
         for (int it = 0; it < niter; it += 2) {
@@ -503,10 +516,16 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
             __syncthreads();
         }
     };
-    pass(std::false_type{});
-    store((nq + nkv + g) * HD, 1.f);
-    pass(std::true_type{});
-    store((nq + g) * HD, scale);
+    if constexpr (ONE_PASS) {
+        pass(std::integral_constant<int, 2>{});
+        store(acc2, (nq + nkv + g) * HD, 1.f);
+        store(acc, (nq + g) * HD, scale);
+    } else {
+        pass(std::integral_constant<int, 0>{});
+        store(acc, (nq + nkv + g) * HD, 1.f);
+        pass(std::integral_constant<int, 1>{});
+        store(acc, (nq + g) * HD, scale);
+    }
 }
 
 // dqkv[:, K and V columns] = bf16(dkv_acc); w = 2 * nkv * HD fp32 per token, 4 per thread
