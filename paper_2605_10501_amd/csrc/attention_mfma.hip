@@ -190,18 +190,25 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
 // delta[h, t] = sum_d dO[t, h, d] O[t, h, d]  (the row term of the softmax Jacobian)
 __global__ __launch_bounds__(256) void attn_delta_kernel(const bf16_t *__restrict__ o, const bf16_t *__restrict__ d_o,
                                                           float *__restrict__ delta, int n, int nq, int hd) {
-    const long idx = (long)blockIdx.x * blockDim.x + threadIdx.x;
-    if (idx >= (long)n * nq) return;
-    const long t = idx / nq;
-    const int h = idx % nq;
-    const bf16_t *a = o + idx * hd, *b = d_o + idx * hd;
+    // 8 lanes per (token, head): consecutive lanes read consecutive 16-byte pieces, so a wave's load is one
+    // contiguous run; the 8 partial sums meet through xor-shuffles
+    const long gid = (long)blockIdx.x * blockDim.x + threadIdx.x;
+    const long idx = gid >> 3;
+    const int sub = (int)(gid & 7);
+    const bool live = idx < (long)n * nq;
     float acc = 0.f;
-    for (int d = 0; d < hd; d += 8) {
-        const Vec16<bf16_t> x = ldv(a + d), y = ldv(b + d);
+    if (live) {
+        const bf16_t *a = o + idx * hd, *b = d_o + idx * hd;
+        for (int d = sub * 8; d < hd; d += 64) {
+            const Vec16<bf16_t> x = ldv(a + d), y = ldv(b + d);
 #pragma unroll
-        for (int e = 0; e < 8; ++e) acc += (float)x.v[e] * (float)y.v[e];
+            for (int e = 0; e < 8; ++e) acc += (float)x.v[e] * (float)y.v[e];
+        }
     }
-    delta[(long)h * n + t] = acc;
+    acc += __shfl_xor(acc, 1, 64);
+    acc += __shfl_xor(acc, 2, 64);
+    acc += __shfl_xor(acc, 4, 64);
+    if (live && sub == 0) delta[(long)(idx % nq) * n + idx / nq] = acc;
 }
 
 // dQ: same decomposition as the forward kernel (workgroup = 128 queries of one head, keys visited
@@ -560,7 +567,7 @@ template <int HD>
 ms_status launch_bwd(int causal, int nq, int nkv, int n, int n_seqs, int max_seqlen, const int *cu, const void *qkv,
                      const void *o, const float *lse, const void *d_o, void *dqkv, void *scratch, hipStream_t s) {
     float *delta = (float *)scratch;
-    attn_delta_kernel<<<ms_cdiv((long)n * nq, 256), 256, 0, s>>>((const bf16_t *)o, (const bf16_t *)d_o, delta, n, nq, HD);
+    attn_delta_kernel<<<ms_cdiv((long)n * nq * 8, 256), 256, 0, s>>>((const bf16_t *)o, (const bf16_t *)d_o, delta, n, nq, HD);
     MS_LAUNCH_CHECK();
     const float scale = 1.f / sqrtf((float)HD);
     const int ntile_max = ms_cdiv(max_seqlen, 128);
