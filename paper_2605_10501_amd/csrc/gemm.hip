@@ -774,7 +774,7 @@ extern "C" ms_status ms_k_gemm(int32_t dtype, int32_t trans_a, int32_t trans_b, 
         return ms_fail(MS_ERR_UNSUPPORTED,
                        "gemm(bf16): contiguous dimension of each operand must be a multiple of 8 and 16-byte aligned "
                        "(M=%d N=%d K=%d ta=%d tb=%d lda=%ld ldb=%ld)", M, N, K, trans_a, trans_b, (long)lda, (long)ldb);
-    GemmParams p;
+    GemmParams p = {};
     p.A = A; p.B = B; p.C = C; p.bias = bias; p.residual = residual;
     p.lda = lda; p.ldb = ldb; p.ldc = ldc; p.ldr = ldr; p.M = M; p.N = N; p.K = K; p.alpha = alpha;
     p.c_fp32 = c_fp32; p.accumulate = accumulate; p.res_fp32 = residual_fp32;
