@@ -113,6 +113,9 @@ def main():
     B.lib()
     dev = "cuda"
     work = wl.workload(args.workload, 0)
+    if work.teacher is None:     # c3 (KD head alone) and c4 (vision encoder forward+backward): secondary workloads
+        print(json.dumps(bench_secondary(work, args, torch, B, wl, dev)))
+        return
     t_cfg, s_cfg, kd = work.teacher, work.student, work.kd
     dt = t_cfg.torch_dtype
     tw, sw = wl.section_weights(t_cfg, 0, "teacher", dev), wl.section_weights(s_cfg, 0, "student", dev)
@@ -270,6 +273,59 @@ def main():
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(work, tw, sw, wt, ws, ids, args.cpu_sample_tokens)
     print(json.dumps(result))
+
+
+def bench_secondary(work, args, torch, B, wl, dev):
+    """c3: the KD head alone on given hidden states; c4: one vision-encoder section forward+backward on a packed
+    micro-batch of image samples.  Same timing protocol as the main step; no roofline object (not the metric's workload)."""
+    dt = torch.bfloat16
+
+    def timed(fn, k):
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(k):
+            fn()
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) / k
+    if work.student is None:
+        kd, n = work.kd, work.n_tokens
+        h_t = wl.normal(0, "c3.ht", (n, kd.h_teacher), 1.0, 0.0, dt, dev)
+        h_s = wl.normal(0, "c3.hs", (n, kd.h_student), 1.0, 0.0, dt, dev)
+        wt = wl.normal(0, "c3.wt", (kd.vocab, kd.h_teacher), 0.02, 0.0, dt, dev)
+        ws = wl.normal(0, "c3.ws", (kd.vocab, kd.h_student), 0.02, 0.0, dt, dev)
+        d_ws = torch.zeros((kd.vocab, kd.h_student), dtype=torch.float32, device=dev)
+        wsb = B.workspace(B.kd_workspace_bytes(kd, n), dev, "kd")
+        fn = lambda: B.kd_loss_forward_backward(kd, wt, ws, h_t, h_s, d_w_student=d_ws, ws=wsb)
+        flops = 2.0 * n * kd.vocab * (kd.h_teacher + kd.h_student) + 4.0 * n * kd.vocab * kd.h_student
+        metric = "KD head tokens/s (both lm_heads, KL loss, gradients to student hidden states and lm_head), 1 GPU"
+        desc = f"{work.name}: {n} tokens, vocab {kd.vocab} in chunks of {kd.chunk}, hidden {kd.h_teacher}/{kd.h_student}, T={kd.temperature:g}"
+    else:
+        cfg = work.student
+        cu = wl.cu_seqlens_of(work.lengths)
+        n, batch = cu[-1], B.Batch(cu)
+        w = wl.section_weights(cfg, 0, "vit", dev)
+        grads = B.zero_grads(w)
+        x = wl.normal(0, "c4.x", (n, cfg.d_model), 1.0, 0.0, dt, dev)
+        dy = wl.normal(0, "c4.dy", (n, cfg.d_model), 1.0, 0.0, dt, dev)
+        wsb = B.workspace(B.section_workspace_bytes(cfg, n, batch.max_seqlen, True), dev, "vit")
+        fn = lambda: B.section_forward_backward(cfg, w, grads, batch, x, d_h_out=dy, ws=wsb)
+        pairs = sum(l * l for l in work.lengths if l)
+        flops = 3 * 2.0 * cfg.layer_params() * n * cfg.n_layers + 3.5 * 4.0 * cfg.n_q_heads * cfg.head_dim * pairs * cfg.n_layers
+        metric = "vision-encoder section forward+backward tokens/s, 1 GPU"
+        desc = f"{work.name}: {n} packed patch tokens, {batch.n_seqs} image samples (max {batch.max_seqlen}), {describe(cfg)}, bidirectional"
+    for _ in range(args.warmup):
+        fn()
+    sec = timed(fn, args.steps)
+    B.profile_enable(1)
+    fn()
+    torch.cuda.synchronize()
+    prof = B.profile_read()
+    B.profile_enable(0)
+    kernels = {k: {"launches": c, "ms": ms} for k, (c, ms, _) in prof.items() if c}
+    return {"metric": metric, "value": n / sec, "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+            "ms_per_step": 1e3 * sec, "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16",
+            "data": "synthetic", "config": {"workload": desc}, "model_tflop_per_step": flops / 1e12,
+            "mfma_frac_whole_step": flops / sec / 1e12 / PEAK_BF16_TFLOPS, "kernels": kernels}
 
 
 def cpu_baseline(work, tw, sw, wt, ws, ids, sample_tokens):
