@@ -177,7 +177,7 @@ def main():
     torch.cuda.synchronize()
     prof = B.profile_read()
     B.profile_enable(0)
-    sweep, adamw, probe_tflops, copy_gbs, variant = [], None, None, None, None
+    sweep, adamw, probe_tflops, probe_rand_tflops, copy_gbs, variant = [], None, None, None, None, None
     if not args.step_only:
         # variant (not the metric): a token block's teacher logits stay in HBM between the two KD passes instead
         # of being recomputed -- [4096, vocab] fp32, independent of the batch size
@@ -216,6 +216,10 @@ def main():
         sink = torch.zeros(512 * 512, dtype=torch.float32, device=dev)
         sec_probe, _ = timed(lambda: B.k_mfma_probe(512, 10000, sink), 3)
         probe_tflops = 512 * 8 * 10000 * 8 * 32768 / sec_probe / 1e12
+        # the same loop on operands with random signs and mantissas: the chip lowers its clock under their bit
+        # activity, so this is the rate a bf16 kernel can approach on real data
+        sec_probe_r, _ = timed(lambda: B.k_mfma_probe(512, 10000, sink, random_operands=True), 3)
+        probe_rand_tflops = 512 * 8 * 10000 * 8 * 32768 / sec_probe_r / 1e12
         src = torch.ones(1 << 30, dtype=torch.uint8, device=dev)
         dst = torch.empty_like(src)
         sec_copy, _ = timed(lambda: B.k_copy(src, dst), 3)
@@ -259,6 +263,7 @@ def main():
         "loss": loss, "logits_to_hidden_ratio": kd.vocab / kd.h_teacher,
         "variant_cached_teacher_logits": variant, "teacher_microbatch_sweep": sweep, "student_adamw_step": adamw,
         "measured_references": None if args.step_only else {"mfma_register_loop_tflops": probe_tflops,
+                                                             "mfma_register_loop_random_operands_tflops": probe_rand_tflops,
                                                              "copy_1gib_read_plus_write_gbs": copy_gbs},
         "roofline": {"kernel": "gemm_bf16_fast_kernel (A[M,K] B[N,K]^T, all forward linears and lm_head chunks)",
                      "bound": "mfma", "achieved": achieved, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",

@@ -113,8 +113,11 @@ ms_status ms_k_copy(const void *src, void *dst, size_t bytes, void *stream);
 /* Register-resident bf16 MFMA loop on every CU (no memory traffic in the loop): the matrix-core rate the chip
  * sustains at its clocks under load, as a reference beside the published peak.  Each of `workgroups` x 8 waves
  * issues iters x 8 independent v_mfma_f32_32x32x16_bf16; sink_dev (>= workgroups * 512 floats) receives one value
- * per lane so that the loop is not removed.  Algorithmic flops = workgroups * 8 * iters * 8 * 32768. */
-ms_status ms_k_mfma_probe(int32_t workgroups, int32_t iters, float *sink_dev, void *stream);
+ * per lane so that the loop is not removed.  Algorithmic flops = workgroups * 8 * iters * 8 * 32768.
+ * random_operands = 0: small constants in the operand registers (lowest bit activity); 1: pseudo-random signs
+ * and mantissas with magnitudes 2^-4 .. 2^4, as real weights and activations have.  The chip's power management
+ * lowers the clock under the second, so the two rates bracket what a bf16 kernel can reach on real data. */
+ms_status ms_k_mfma_probe(int32_t workgroups, int32_t iters, int32_t random_operands, float *sink_dev, void *stream);
 
 #ifdef __cplusplus
 }

@@ -916,7 +916,7 @@ ms_status gemm_swiglu(int M, int F, int K, const void *A, long lda, const void *
 
 // ------------------------------------------------------------------ matrix-core rate probe
 namespace {
-__global__ __launch_bounds__(512) void mfma_probe_kernel(int iters, float *sink) {
+__global__ __launch_bounds__(512) void mfma_probe_kernel(int iters, int random_operands, float *sink) {
     f32x16 acc[8];
 #pragma unroll
     for (int i = 0; i < 8; ++i)
@@ -925,6 +925,19 @@ __global__ __launch_bounds__(512) void mfma_probe_kernel(int iters, float *sink)
     bf16x8 a, b;
 #pragma unroll
     for (int e = 0; e < 8; ++e) { a[e] = (bf16_t)(float)(threadIdx.x & 3); b[e] = (bf16_t)(1.f / 64.f); }
+    if (random_operands) {
+        // random sign and mantissa, magnitudes 2^-4 .. 2^4: the bit activity of real activations and weights,
+        // which is what the chip's power management reacts to
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            unsigned h = (threadIdx.x * 8u + e) * 2654435761u + blockIdx.x * 40503u;
+            h ^= h >> 15; h *= 2246822519u; h ^= h >> 13;
+            unsigned g = h * 2654435761u + 12345u;
+            g ^= g >> 16; g *= 2246822519u; g ^= g >> 13;
+            a[e] = __builtin_bit_cast(bf16_t, (unsigned short)(((h & 1) << 15) | ((123 + ((h >> 1) & 7)) << 7) | ((h >> 4) & 127)));
+            b[e] = __builtin_bit_cast(bf16_t, (unsigned short)(((g & 1) << 15) | ((123 + ((g >> 1) & 7)) << 7) | ((g >> 4) & 127)));
+        }
+    }
     for (int it = 0; it < iters; ++it) {
 #pragma unroll
         for (int i = 0; i < 8; ++i) acc[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, acc[i], 0, 0, 0);
@@ -938,9 +951,9 @@ __global__ __launch_bounds__(512) void mfma_probe_kernel(int iters, float *sink)
 }
 }  // namespace
 
-extern "C" ms_status ms_k_mfma_probe(int32_t workgroups, int32_t iters, float *sink_dev, void *stream) {
+extern "C" ms_status ms_k_mfma_probe(int32_t workgroups, int32_t iters, int32_t random_operands, float *sink_dev, void *stream) {
     if (workgroups <= 0 || iters <= 0 || !sink_dev) return ms_fail(MS_ERR_INVALID_ARG, "mfma_probe: bad argument");
-    mfma_probe_kernel<<<workgroups, 512, 0, (hipStream_t)stream>>>(iters, sink_dev);
+    mfma_probe_kernel<<<workgroups, 512, 0, (hipStream_t)stream>>>(iters, random_operands, sink_dev);
     MS_LAUNCH_CHECK();
     return MS_OK;
 }

@@ -215,6 +215,12 @@ def test_mfma_probe_counts_what_it_claims():
     B.k_mfma_probe(4, 10, sink)
     torch.cuda.synchronize()
     assert torch.all(sink == 480.0)
+    # random operands: same instruction stream, data-dependent values; finite and reproducible
+    B.k_mfma_probe(4, 10, sink, random_operands=True)
+    first = sink.clone()
+    B.k_mfma_probe(4, 10, sink, random_operands=True)
+    torch.cuda.synchronize()
+    assert torch.isfinite(sink).all() and torch.equal(sink, first) and float(sink.abs().max()) > 0
 
 
 @pytest.mark.parametrize("wdtype", [torch.bfloat16, torch.float32])
