@@ -178,6 +178,22 @@ def main():
     prof = B.profile_read()
     B.profile_enable(0)
     sweep, adamw, probe_tflops, probe_rand_tflops, copy_gbs, variant = [], None, None, None, None, None
+    clocks = {}
+    side = torch.cuda.Stream()
+    clk = torch.zeros(2, dtype=torch.int64, device=dev)
+
+    def clock_during(fn, reps, microseconds):
+        """Average shader clock (MHz) while `reps` x fn run: fn is queued on the main stream, then one wave on a
+        second stream compares the shader-clock counter with the constant 100 MHz counter for `microseconds`."""
+        torch.cuda.synchronize()
+        for _ in range(reps):
+            fn()
+        with torch.cuda.stream(side):
+            B.k_clock_monitor(microseconds, clk)
+        torch.cuda.synchronize()
+        c, w = clk.tolist()
+        return 100.0 * c / max(w, 1)
+
     if not args.step_only:
         # variant (not the metric): a token block's teacher logits stay in HBM between the two KD passes instead
         # of being recomputed -- [4096, vocab] fp32, independent of the batch size
@@ -220,6 +236,10 @@ def main():
         # activity, so this is the rate a bf16 kernel can approach on real data
         sec_probe_r, _ = timed(lambda: B.k_mfma_probe(512, 10000, sink, random_operands=True), 3)
         probe_rand_tflops = 512 * 8 * 10000 * 8 * 32768 / sec_probe_r / 1e12
+        clocks["mfma_register_loop"] = clock_during(lambda: B.k_mfma_probe(512, 10000, sink), 4, int(3e6 * sec_probe))
+        clocks["mfma_register_loop_random_operands"] = clock_during(
+            lambda: B.k_mfma_probe(512, 10000, sink, random_operands=True), 4, int(3e6 * sec_probe_r))
+        clocks["whole_step"] = clock_during(step, 3, int(2e6 * sec_step))
         src = torch.ones(1 << 30, dtype=torch.uint8, device=dev)
         dst = torch.empty_like(src)
         sec_copy, _ = timed(lambda: B.k_copy(src, dst), 3)
@@ -264,6 +284,7 @@ def main():
         "variant_cached_teacher_logits": variant, "teacher_microbatch_sweep": sweep, "student_adamw_step": adamw,
         "measured_references": None if args.step_only else {"mfma_register_loop_tflops": probe_tflops,
                                                              "mfma_register_loop_random_operands_tflops": probe_rand_tflops,
+                                                             "shader_clock_mhz": clocks,
                                                              "copy_1gib_read_plus_write_gbs": copy_gbs},
         "roofline": {"kernel": "gemm_bf16_fast_kernel (A[M,K] B[N,K]^T, all forward linears and lm_head chunks)",
                      "bound": "mfma", "achieved": achieved, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",

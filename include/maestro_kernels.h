@@ -119,6 +119,12 @@ ms_status ms_k_copy(const void *src, void *dst, size_t bytes, void *stream);
  * lowers the clock under the second, so the two rates bracket what a bf16 kernel can reach on real data. */
 ms_status ms_k_mfma_probe(int32_t workgroups, int32_t iters, int32_t random_operands, float *sink_dev, void *stream);
 
+/* Clock monitor: one wave that runs for about `microseconds` (1 .. 1000000; bounded by a poll count as well) and
+ * writes to out_dev[0] the shader-clock cycles and to out_dev[1] the ticks of the constant 100 MHz counter that
+ * passed meanwhile: average shader clock = 100 MHz * out_dev[0] / out_dev[1].  Launched on a second stream it
+ * reports the clock the chip's power management grants while the kernels of another stream run. */
+ms_status ms_k_clock_monitor(int32_t microseconds, int64_t *out_dev, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -410,6 +410,11 @@ def k_mfma_probe(workgroups, iters, sink, random_operands=False):
     _check(lib().ms_k_mfma_probe(workgroups, iters, int(random_operands), _p(sink), _stream()))
 
 
+def k_clock_monitor(microseconds, out):
+    """out: int64[2] device tensor; launched on the current stream."""
+    _check(lib().ms_k_clock_monitor(int(microseconds), _p(out), _stream()))
+
+
 def k_copy(src, dst):
     _check(lib().ms_k_copy(_p(src), _p(dst), C.c_size_t(src.numel() * src.element_size()), _stream()))
     return dst

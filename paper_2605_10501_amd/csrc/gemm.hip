@@ -949,7 +949,30 @@ __global__ __launch_bounds__(512) void mfma_probe_kernel(int iters, int random_o
         for (int r = 0; r < 16; ++r) t += acc[i][r];
     sink[(long)blockIdx.x * 512 + threadIdx.x] = t;
 }
+
+// One wave that watches the clocks for a given time while other kernels run: the shader-clock counter
+// (s_memtime) against the constant 100 MHz counter (s_memrealtime).  Ends after `ticks_100mhz` of the constant
+// counter or after max_polls polls, whichever comes first.
+__global__ __launch_bounds__(64) void clock_monitor_kernel(long ticks_100mhz, long max_polls, long long *out) {
+    const long long c0 = clock64(), w0 = wall_clock64();
+    long long w1 = w0;
+    for (long i = 0; i < max_polls && w1 - w0 < ticks_100mhz; ++i) {
+        __builtin_amdgcn_s_sleep(64);
+        w1 = wall_clock64();
+    }
+    const long long c1 = clock64();
+    w1 = wall_clock64();
+    if (threadIdx.x == 0) { out[0] = c1 - c0; out[1] = w1 - w0; }
+}
 }  // namespace
+
+extern "C" ms_status ms_k_clock_monitor(int32_t microseconds, int64_t *out_dev, void *stream) {
+    if (microseconds <= 0 || microseconds > 1000000 || !out_dev) return ms_fail(MS_ERR_INVALID_ARG, "clock_monitor: bad argument");
+    // a poll takes at least the 64 x 64 clocks of its sleep (> 1.5 us at any clock this chip runs at)
+    clock_monitor_kernel<<<1, 64, 0, (hipStream_t)stream>>>(100L * microseconds, 2L * microseconds + 1000, (long long *)out_dev);
+    MS_LAUNCH_CHECK();
+    return MS_OK;
+}
 
 extern "C" ms_status ms_k_mfma_probe(int32_t workgroups, int32_t iters, int32_t random_operands, float *sink_dev, void *stream) {
     if (workgroups <= 0 || iters <= 0 || !sink_dev) return ms_fail(MS_ERR_INVALID_ARG, "mfma_probe: bad argument");

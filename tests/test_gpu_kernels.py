@@ -223,6 +223,15 @@ def test_mfma_probe_counts_what_it_claims():
     assert torch.isfinite(sink).all() and torch.equal(sink, first) and float(sink.abs().max()) > 0
 
 
+def test_clock_monitor_ends_on_time_and_reports_a_plausible_clock():
+    out = torch.zeros(2, dtype=torch.int64, device="cuda")
+    B.k_clock_monitor(2000, out)
+    torch.cuda.synchronize()
+    cycles, ticks = out.tolist()
+    assert 2000 * 100 <= ticks <= 2000 * 100 * 1.2            # the constant counter runs at 100 MHz
+    assert 300.0 <= 100.0 * cycles / ticks <= 3000.0           # MHz
+
+
 @pytest.mark.parametrize("wdtype", [torch.bfloat16, torch.float32])
 def test_adamw_step_matches_oracle(wdtype):
     from oracle.optimizer import adamw_step
