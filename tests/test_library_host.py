@@ -66,6 +66,15 @@ def test_errors_are_detected_on_the_host_without_a_gpu():
     assert _call_forward(cu=(0, 0), n_tokens=0) == 0                              # skipped section: no-op
 
 
+def test_probe_arguments_are_checked_before_any_launch():
+    lib = B.lib()
+    assert lib.ms_k_clock_monitor(0, C.c_void_p(256), None) == -1
+    assert lib.ms_k_clock_monitor(2_000_000, C.c_void_p(256), None) == -1        # longer than a second
+    assert lib.ms_k_clock_monitor(100, None, None) == -1 and b"clock_monitor" in lib.ms_last_error()
+    assert lib.ms_k_mfma_probe(0, 10, 0, C.c_void_p(256), None) == -1
+    assert lib.ms_k_mfma_probe(4, 10, 1, None, None) == -1
+
+
 def test_workspace_sizes():
     c2 = wl.workload("c2")
     fwd = B.section_workspace_bytes(c2.teacher, 16384, 4096, False)
