@@ -19,6 +19,13 @@
 extern "C" {
 #endif
 
+/* Kernel selection of the bf16 GEMMs, for measurements and tests (host-side switch, affects later launches
+ * from any thread; not meant to be changed while launches are being issued).  tile: 0 = automatic (by shape),
+ * 128 or 256 = force that workgroup tile for the direct-to-LDS kernels, -1 = use only the generic kernel.
+ * mfma16: 1 = v_mfma_f32_16x16x32_bf16, 0 = v_mfma_f32_32x32x16_bf16, -1 = default.  The process-wide defaults
+ * come from the environment (MS_GEMM_TILE, MS_GEMM_MFMA16). */
+ms_status ms_k_gemm_config(int32_t tile, int32_t mfma16);
+
 /* C[M,N] = alpha * sum_k A(m,k) B(n,k) (+ bias[n]) (+ residual[m,n]), optionally C += .
  * trans_a = 0: A is [M,K] row-major (lda); 1: A is stored [K,M] (lda).
  * trans_b = 0: B is [N,K] row-major (ldb); 1: B is stored [K,N] (ldb).

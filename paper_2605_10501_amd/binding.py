@@ -291,6 +291,11 @@ def schedule_makespan(tuples, order, interleave=True):
 
 
 # ------------------------------------------------------------------ kernel-level entry points
+def k_gemm_config(tile=0, mfma16=-1):
+    """Kernel selection of the bf16 GEMMs (tests, measurements): tile 0 / 128 / 256 / -1, mfma16 -1 / 0 / 1."""
+    _check(lib().ms_k_gemm_config(int(tile), int(mfma16)))
+
+
 def k_gemm(a, b, trans_a=False, trans_b=False, c=None, c_fp32=False, accumulate=False, bias=None, residual=None,
            alpha=1.0, split_k=1, dtype=None):
     res_fp32 = residual is not None and residual.dtype == torch.float32 and a.dtype == torch.bfloat16

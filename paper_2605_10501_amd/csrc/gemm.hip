@@ -268,6 +268,12 @@ template <int R, int PER, int... I>
 __device__ __forceinline__ void sched_pairs(std::integer_sequence<int, I...>) {
     (sched_reads_then_mfma<((I + 1) * PER <= R ? PER : R - I * PER)>(), ...);
 }
+// Scheduling pattern of one k-step with 16-row fragments: per row block, its NB MFMAs and then the reads that
+// refill its A fragment (RA reads) and, behind the first NB row blocks, one B fragment (RB reads).
+template <int NB, int RA, int RB, int... I>
+__device__ __forceinline__ void sched_mfma_then_reads(std::integer_sequence<int, I...>) {
+    ((__builtin_amdgcn_sched_group_barrier(0x008, NB, 0), __builtin_amdgcn_sched_group_barrier(0x100, RA + (I < NB ? RB : 0), 0)), ...);
+}
 template <int R, int M>
 __device__ __forceinline__ void interleave_reads_with_mfma() {
     constexpr int PER = R >= M ? (R + M - 1) / M : 1;     // reads in front of each of the first MFMAs
@@ -277,10 +283,61 @@ __device__ __forceinline__ void interleave_reads_with_mfma() {
     if constexpr (M > PAIRS) __builtin_amdgcn_sched_group_barrier(0x008, M - PAIRS, 0);
 }
 
-template <int BM, int BN, int WM, int WN, bool TA, bool TB, int EPI = EPI_NONE>
+// Addresses of the transposing reads of a K-major operand for v_mfma_f32_16x16x32_bf16: the 16 lanes of group g
+// (= lane / 16) read k rows 8g .. 8g+7 of the k-step (two reads of four rows) for the 16 columns of a block.
+// The LDS swizzle of those rows does not depend on the k-step, and the two 16-column halves of a 32-column
+// block differ by one flipped chunk bit: four registers per operand, everything else is a constant offset.
+struct TrFragAddr16 {
+    int base[2][2];   // [16-column half of the 32-column block][first / second read], element offset within the tile
+    __device__ __forceinline__ void init(int w32, int lane) {
+        const int g = lane >> 4, r = lane & 15, q = r >> 2;
+#pragma unroll
+        for (int hf = 0; hf < 2; ++hf) {
+            const int m = w32 * 32 + 16 * hf + 4 * (r & 3);
+            const int sub = m >> 6, chunk = (m & 63) >> 3;
+#pragma unroll
+            for (int rd = 0; rd < 2; ++rd) {
+                const int rl = 8 * g + q + 4 * rd;                       // row within the 32-row k-step
+                const int sw = (rl & 7) ^ ((rl >> 3) & 3);
+                base[hf][rd] = sub * 4096 + rl * 64 + ((chunk ^ sw) << 3) + (m & 7);
+            }
+        }
+    }
+    // block16 = index of the wave's 16-column block; off = element offset of its 32-column block's sub-tile pair
+    __device__ __forceinline__ bf16x8 frag(const bf16_t *tile, int kk, int block16, int off) const {
+        return tr_frag(tile + base[block16 & 1][0] + kk * 2048 + off, tile + base[block16 & 1][1] + kk * 2048 + off);
+    }
+};
+
+// Addresses of the 16-byte fragment reads of a K-contiguous operand for v_mfma_f32_16x16x32_bf16: lane = (row
+// lane % 16 of the 16-row block, k-group lane / 16).  The LDS swizzle makes the chunk position depend on the
+// parity of the block and on the k-step; four registers per operand cover all blocks with constant offsets.
+struct KFragAddr16 {
+    int base[2][2];   // [block parity][k-step], element offset within the tile of block 0 / 1
+    __device__ __forceinline__ void init(int row0, int lane) {      // row0 = first tile row of the wave (multiple of 32)
+        const int r = lane & 15, g = lane >> 4;
+#pragma unroll
+        for (int par = 0; par < 2; ++par)
+#pragma unroll
+            for (int kk = 0; kk < 2; ++kk) base[par][kk] = lds_off(row0 + par * 16 + r, kk * 4 + g) - par * 16 * BK;
+    }
+    __device__ __forceinline__ bf16x8 frag(const bf16_t *tile, int kk, int block16) const {
+        return *(const bf16x8 *)(tile + base[block16 & 1][kk] + block16 * 16 * BK);
+    }
+};
+
+// M16 selects v_mfma_f32_16x16x32_bf16 (16-row fragments, two k-steps of 32 per K tile) instead of
+// v_mfma_f32_32x32x16_bf16 (32-row fragments, four k-steps of 16): the same LDS traffic and the same number of
+// accumulator registers, but on operands with realistic bit activity the chip sustains a higher clock on it.
+template <int BM, int BN, int WM, int WN, bool TA, bool TB, int EPI = EPI_NONE, bool M16 = false>
 __global__ __launch_bounds__(64 * WM * WN) void gemm_bf16_fast_kernel(GemmParams p) {
     constexpr int NT = 64 * WM * WN;
-    constexpr int WTM = BM / WM, WTN = BN / WN, MI = WTM / 32, NI = WTN / 32;
+    constexpr int FR = M16 ? 16 : 32;                         // rows of an MFMA fragment / accumulator block
+    constexpr int KSTEP = M16 ? 32 : 16, KS = BK / KSTEP;     // contraction depth of an MFMA, k-steps per K tile
+    constexpr int WTM = BM / WM, WTN = BN / WN, MI = WTM / FR, NI = WTN / FR;
+    constexpr int MI32 = WTM / 32, NI32 = WTN / 32;           // the epilogues work on 32-row blocks
+    using acc_t = std::conditional_t<M16, f32x4, f32x16>;
+    constexpr int ACC_N = M16 ? 4 : 16;
     // four separate LDS objects (not one carved array): the compiler orders LDS reads against
     // in-flight direct-to-LDS loads by alias analysis, and can only tell the buffer being filled
     // from the buffer being read when they are distinct objects
@@ -323,13 +380,13 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_bf16_fast_kernel(GemmParams
     else if constexpr (TB) db.init(p.ldb, n0, wave, lane);
     else db.init(p.ldb, n0, lane);
 
-    f32x16 acc[MI][NI];
+    acc_t acc[MI][NI];
 #pragma unroll
     for (int i = 0; i < MI; ++i)
 #pragma unroll
         for (int j = 0; j < NI; ++j)
 #pragma unroll
-            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+            for (int r = 0; r < ACC_N; ++r) acc[i][j][r] = 0.f;
 
     // Start moving K tile kt towards LDS; a tile past the end of this workgroup's K range arrives as zeros.
     // An operand stored K-major ([K][M]) is loaded as a "row tile" (64 k-rows x BM columns) and read back
@@ -341,58 +398,95 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_bf16_fast_kernel(GemmParams
         da.issue(ra, as, k0, wave, inv);
         db.issue(rb, bs, k0, wave, inv);
     };
-    const int frow = lane & 31, fhalf = lane >> 5;
+    // lane -> (fragment row, k-group of 8 consecutive k): 32 rows x 2 groups, or 16 rows x 4 groups
+    const int frow = lane & (FR - 1), fhalf = lane / FR;
     // 32-row block i (32-column block j) of this wave within the tile.  For a K-major operand the blocks
     // of a wave are spread one per 64-wide LDS sub-tile pair so that all of them share one LDS address
     // register (constant offsets); for a K-contiguous operand they are adjacent for the same reason.
     auto row_base = [&](int i) { return TA ? i * (32 * WM) + wm * 32 : wm * WTM + i * 32; };
     auto col_base = [&](int j) { return TB ? j * (32 * WN) + wn * 32 : wn * WTN + j * 32; };
+    // the same for fragment blocks (16-row blocks are the halves of the 32-row blocks)
+    auto frow_base = [&](int i) { return M16 ? row_base(i >> 1) + (i & 1) * 16 : row_base(i); };
+    auto fcol_base = [&](int j) { return M16 ? col_base(j >> 1) + (j & 1) * 16 : col_base(j); };
     // Operand fragments are double-buffered in registers: the LDS reads of k-step kk+1 are issued between
     // the MFMAs of k-step kk.
     bf16x8 af[2][MI], bfr[2][NI];
-    TrFragAddr tra, trb;
+    std::conditional_t<M16, TrFragAddr16, TrFragAddr> tra, trb;
     if constexpr (TA) tra.init(wm, lane);     // block i of the wave: columns i * 32 * WM + wm * 32 of the row tile
     if constexpr (TB) trb.init(wn, lane);
+    KFragAddr16 ka, kb;
+    if constexpr (M16 && !TA) ka.init(wm * WTM, lane);
+    if constexpr (M16 && !TB) kb.init(wn * WTN, lane);
+    auto load_a = [&](const bf16_t *as, int kk, int slot, int i) {
+        if constexpr (TA && M16) af[slot][i] = tra.frag(as, kk, i, (i >> 1) * (32 * WM / 64) * 4096);
+        else if constexpr (TA) af[slot][i] = tra.frag(as, kk, i * (32 * WM / 64) * 4096);
+        else if constexpr (M16) af[slot][i] = ka.frag(as, kk, i);
+        else af[slot][i] = *(const bf16x8 *)(as + lds_off(frow_base(i) + frow, kk * (KSTEP / 8) + fhalf));
+    };
+    auto load_b = [&](const bf16_t *bs, int kk, int slot, int j) {
+        if constexpr (TB && M16) bfr[slot][j] = trb.frag(bs, kk, j, (j >> 1) * (32 * WN / 64) * 4096);
+        else if constexpr (TB) bfr[slot][j] = trb.frag(bs, kk, j * (32 * WN / 64) * 4096);
+        else if constexpr (M16) bfr[slot][j] = kb.frag(bs, kk, j);
+        else bfr[slot][j] = *(const bf16x8 *)(bs + lds_off(fcol_base(j) + frow, kk * (KSTEP / 8) + fhalf));
+    };
     auto load_frags = [&](const bf16_t *as, const bf16_t *bs, int kk, int slot) {
 #pragma unroll
-        for (int i = 0; i < MI; ++i) {
-            const int row = row_base(i);
-            if constexpr (TA) af[slot][i] = tra.frag(as, kk, i * (32 * WM / 64) * 4096);
-            else af[slot][i] = *(const bf16x8 *)(as + lds_off(row + frow, kk * 2 + fhalf));
-        }
+        for (int i = 0; i < MI; ++i) load_a(as, kk, slot, i);
 #pragma unroll
-        for (int j = 0; j < NI; ++j) {
-            const int row = col_base(j);
-            if constexpr (TB) bfr[slot][j] = trb.frag(bs, kk, j * (32 * WN / 64) * 4096);
-            else bfr[slot][j] = *(const bf16x8 *)(bs + lds_off(row + frow, kk * 2 + fhalf));
-        }
+        for (int j = 0; j < NI; ++j) load_b(bs, kk, slot, j);
     };
     auto mfma_step = [&](int slot) {
 #pragma unroll
         for (int i = 0; i < MI; ++i)
 #pragma unroll
-            for (int j = 0; j < NI; ++j)
-                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[slot][i], bfr[slot][j], acc[i][j], 0, 0, 0);
+            for (int j = 0; j < NI; ++j) {
+                if constexpr (M16) acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(af[slot][i], bfr[slot][j], acc[i][j], 0, 0, 0);
+                else acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[slot][i], bfr[slot][j], acc[i][j], 0, 0, 0);
+            }
     };
     constexpr int LDS_READS = (TA ? 2 : 1) * MI + (TB ? 2 : 1) * NI, MFMAS = MI * NI;
+    // One k-step: the MFMAs on fragment slot `cur`, with the reads of the next k-step's fragments (tile la / lb,
+    // k-step lkk) between them.  With 32-row fragments all reads go in front (one per MFMA).  With 16-row
+    // fragments there are twice as many fragment registers per k-step, so the A fragment of row block i is
+    // read right after the MFMAs of row block i, into the registers those MFMAs have just released; only the
+    // B fragments are held twice.
+    auto step = [&](auto cur_c, const bf16_t *la, const bf16_t *lb, int lkk) __attribute__((always_inline)) {
+        constexpr int cur = decltype(cur_c)::value;          // compile-time: the fragment arrays must stay registers
+        if constexpr (M16) {
+            static_assert(NI <= MI, "B fragments are read behind the first NI row blocks");
+#pragma unroll
+            for (int i = 0; i < MI; ++i) {
+#pragma unroll
+                for (int j = 0; j < NI; ++j)
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(af[cur][i], bfr[cur][j], acc[i][j], 0, 0, 0);
+                load_a(la, lkk, cur ^ 1, i);
+                if (i < NI) load_b(lb, lkk, cur ^ 1, i);
+            }
+            sched_mfma_then_reads<NI, (TA ? 2 : 1), (TB ? 2 : 1)>(std::make_integer_sequence<int, MI>{});
+        } else {
+            load_frags(la, lb, lkk, cur ^ 1);
+            mfma_step(cur);
+            interleave_reads_with_mfma<LDS_READS, MFMAS>();
+        }
+        __builtin_amdgcn_sched_barrier(0);
+    };
     // One K tile: steps 0..2 read the next step's fragments from the same tile; before the last step the
     // next tile has landed (own loads: vmcnt(0); the other waves': barrier) and everybody is done reading
     // this one, so its buffers are handed to the tile after next and the last step reads the first
     // fragments of the next tile.  One barrier per tile.
-    auto tile = [&](const bf16_t *ca, const bf16_t *cb, const bf16_t *na, const bf16_t *nb, bf16_t *fa, bf16_t *fb, int kt_fetch) {
-#pragma unroll
-        for (int kk = 0; kk < BK / 16 - 1; ++kk) {
-            load_frags(ca, cb, kk + 1, (kk + 1) & 1);
-            mfma_step(kk & 1);
-            interleave_reads_with_mfma<LDS_READS, MFMAS>();
-            __builtin_amdgcn_sched_barrier(0);
+    auto tile = [&](const bf16_t *ca, const bf16_t *cb, const bf16_t *na, const bf16_t *nb, bf16_t *fa, bf16_t *fb,
+                    int kt_fetch) __attribute__((always_inline)) {
+        using S0 = std::integral_constant<int, 0>;
+        using S1 = std::integral_constant<int, 1>;
+        static_assert(KS == 2 || KS == 4, "k-steps per K tile");
+        step(S0{}, ca, cb, 1);
+        if constexpr (KS == 4) {
+            step(S1{}, ca, cb, 2);
+            step(S0{}, ca, cb, 3);
         }
         __syncthreads();
         fetch(kt_fetch, fa, fb);
-        load_frags(na, nb, 0, 0);
-        mfma_step((BK / 16 - 1) & 1);
-        interleave_reads_with_mfma<LDS_READS, MFMAS>();
-        __builtin_amdgcn_sched_barrier(0);
+        step(S1{}, na, nb, 0);
     };
 
     fetch(0, As0, Bs0);
@@ -407,6 +501,43 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_bf16_fast_kernel(GemmParams
     }
     __syncthreads();   // the (all-zero) tiles still in flight must land before the epilogue reuses LDS
 
+    // ---- epilogue staging: the accumulators of the wave's 32-row block i go to LDS as [32 rows][64 columns]
+    // fp32 (v = value transform), from where each lane reads 4 consecutive columns of a row.  The 16-column
+    // group index (32x32 MFMA: column bit 5 only) is XOR-ed with row bits so that the lanes of one store
+    // instruction, which hold the same columns of rows 4 apart, use different banks.
+    auto stg_swz = [](int row) { return M16 ? ((row >> 2) & 3) << 4 : ((row >> 2) & 1) << 5; };
+    // The lanes of a wave exchange data through the staging area, and the LDS executes a wave's accesses in
+    // program order; what has to be kept is the program order itself: to the compiler a lane's reads and another
+    // lane's writes are unrelated addresses that it may reorder.  wave_sync() is a compiler-level fence between the
+    // two phases (no instruction).
+    auto wave_sync = []() __attribute__((always_inline)) {
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    };
+    auto stage_block = [&](float *stg, int i, auto v) __attribute__((always_inline)) {
+        wave_sync();     // the reads of the previous block come first
+        if constexpr (M16) {
+#pragma unroll
+            for (int h = 0; h < 2; ++h)
+#pragma unroll
+                for (int j = 0; j < NI; ++j)
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) {
+                        const int row = h * 16 + 4 * fhalf + r;
+                        stg[row * 64 + ((j * 16 + frow) ^ stg_swz(row))] = v(acc[2 * i + h][j][r]);
+                    }
+        } else {
+#pragma unroll
+            for (int j = 0; j < NI; ++j)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    const int row = 8 * (r >> 2) + 4 * fhalf + (r & 3);
+                    stg[row * 64 + ((j * 32 + frow) ^ stg_swz(row))] = v(acc[i][j][r]);
+                }
+        }
+        wave_sync();     // every lane's values are in LDS before any lane reads
+    };
     // ---- epilogue.  C and the residual are addressed through buffer descriptors: rows past M are
     // dropped (stores) or read as zero by the range check, columns past N by one select.
     const int esz = p.c_fp32 ? 4 : 2;
@@ -418,7 +549,7 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_bf16_fast_kernel(GemmParams
         // acc[i][0] = gate, acc[i][1] = up of output columns n0/2 + wn*32 + (0..31).  Both are rounded to
         // the storage type first (they are the values a separate activation kernel would read back), staged
         // through LDS as [32 rows][gate 32 | up 32], and each lane then owns 4 consecutive output columns.
-        static_assert(WTN == 64 && NI == 2 && !TA && !TB, "SwiGLU epilogue is built for the K-contiguous layout");
+        static_assert(WTN == 64 && NI32 == 2 && !TA && !TB, "SwiGLU epilogue is built for the K-contiguous layout");
         constexpr int WPA = BM / 64;
         float *stg = (float *)((wave / WPA) ? As1 : As0) + (wave % WPA) * 2048;
         const int prow = lane >> 3, pcol = (lane & 7) * 4;
@@ -432,18 +563,12 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_bf16_fast_kernel(GemmParams
             return w;
         };
 #pragma unroll
-        for (int i = 0; i < MI; ++i) {
-#pragma unroll
-            for (int j = 0; j < NI; ++j)
-#pragma unroll
-                for (int r = 0; r < 16; ++r) {
-                    const int row = 8 * (r >> 2) + 4 * fhalf + (r & 3);
-                    stg[row * 64 + ((j * 32 + frow) ^ (fhalf << 5))] = (float)(bf16_t)(acc[i][j][r] * p.alpha);
-                }
+        for (int i = 0; i < MI32; ++i) {
+            stage_block(stg, i, [&](float a) { return (float)(bf16_t)(a * p.alpha); });
 #pragma unroll
             for (int ps = 0; ps < 4; ++ps) {
                 const int row = ps * 8 + prow;
-                const int flip = ((row >> 2) & 1) << 5;
+                const int flip = stg_swz(row);
                 const float4 g4 = *(const float4 *)(stg + row * 64 + (pcol ^ flip));
                 const float4 u4 = *(const float4 *)(stg + row * 64 + ((32 + pcol) ^ flip));
                 const float gv[4] = {g4.x, g4.y, g4.z, g4.w}, uv[4] = {u4.x, u4.y, u4.z, u4.w};
@@ -520,21 +645,13 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_bf16_fast_kernel(GemmParams
         const float it = p.kd_inv_t;
         if (has_aux) prefetch(0, aux[0], lsev[0]);
 #pragma unroll
-        for (int i = 0; i < MI; ++i) {
-            if (has_aux && i + 1 < MI) prefetch(i + 1, aux[(i + 1) & 1], lsev[(i + 1) & 1]);
-            // accumulators -> LDS [32 rows][64 columns] fp32; column bit 5 is flipped for rows 4..7 (mod 8)
-            // so that the two half-waves (rows 4 apart) use different banks
-#pragma unroll
-            for (int j = 0; j < NI; ++j)
-#pragma unroll
-                for (int r = 0; r < 16; ++r) {
-                    const int row = 8 * (r >> 2) + 4 * fhalf + (r & 3);
-                    stg[row * 64 + ((j * 32 + frow) ^ (fhalf << 5))] = acc[i][j][r] * p.alpha;
-                }
+        for (int i = 0; i < MI32; ++i) {
+            if (has_aux && i + 1 < MI32) prefetch(i + 1, aux[(i + 1) & 1], lsev[(i + 1) & 1]);
+            stage_block(stg, i, [&](float a) { return a * p.alpha; });
 #pragma unroll
             for (int ps = 0; ps < 8; ++ps) {
                 const int row = ps * 4 + prow;
-                const float4 t = *(const float4 *)(stg + row * 64 + (pcol ^ (((row >> 2) & 1) << 5)));
+                const float4 t = *(const float4 *)(stg + row * 64 + (pcol ^ stg_swz(row)));
                 const long rowg = m0 + row_base(i) + row;
                 const u32x4 q = aux[i & 1][ps];
                 const unsigned co = cok ? (unsigned)((rowg * p.ldc + colg) * esz) : kOob;
@@ -613,14 +730,14 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_bf16_fast_kernel(GemmParams
     // scalar epilogue: split-K atomics and shapes whose rows are not 4-element aligned
 #pragma unroll
     for (int j = 0; j < NI; ++j) {
-        const int col = n0 + col_base(j) + frow;
+        const int col = n0 + fcol_base(j) + frow;
         const bool cok = col < p.N;
         const float bv = (bias && cok) ? (float)bias[col] : 0.f;
 #pragma unroll
         for (int i = 0; i < MI; ++i) {
 #pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const int row = m0 + row_base(i) + 8 * (r >> 2) + 4 * fhalf + (r & 3);
+            for (int r = 0; r < ACC_N; ++r) {
+                const int row = m0 + frow_base(i) + (M16 ? 4 * fhalf + r : 8 * (r >> 2) + 4 * fhalf + (r & 3));
                 float v = acc[i][j][r] * p.alpha + bv;
                 if (p.residual) {
                     const unsigned ro = cok ? (unsigned)(((long)row * p.ldr + col) * rsz) : kOob;
@@ -698,22 +815,51 @@ __global__ __launch_bounds__(256) void gemm_f32_kernel(GemmF32Params p) {
 
 // Explicit instantiations: the host pass has been seen to reference the launch stubs of some of these
 // without defining them when they are only instantiated implicitly from the launcher below.
-#define MS_INST(BM, WN, TA, TB) template __global__ void gemm_bf16_fast_kernel<BM, BM, 2, WN, TA, TB>(GemmParams)
+#define MS_INST(BM, WN, TA, TB)                                                                          \
+    template __global__ void gemm_bf16_fast_kernel<BM, BM, 2, WN, TA, TB, EPI_NONE, false>(GemmParams); \
+    template __global__ void gemm_bf16_fast_kernel<BM, BM, 2, WN, TA, TB, EPI_NONE, true>(GemmParams)
 MS_INST(256, 4, false, false); MS_INST(256, 4, false, true); MS_INST(256, 4, true, false); MS_INST(256, 4, true, true);
 MS_INST(128, 2, false, false); MS_INST(128, 2, false, true); MS_INST(128, 2, true, false); MS_INST(128, 2, true, true);
 #undef MS_INST
-template __global__ void gemm_bf16_fast_kernel<256, 256, 2, 4, false, false, EPI_KD_DZ>(GemmParams);
-template __global__ void gemm_bf16_fast_kernel<256, 256, 2, 4, false, false, EPI_KD_STATS>(GemmParams);
-template __global__ void gemm_bf16_fast_kernel<128, 128, 2, 2, false, false, EPI_KD_DZ>(GemmParams);
-template __global__ void gemm_bf16_fast_kernel<128, 128, 2, 2, false, false, EPI_KD_STATS>(GemmParams);
-template __global__ void gemm_bf16_fast_kernel<256, 256, 2, 4, false, false, EPI_SWIGLU>(GemmParams);
-template __global__ void gemm_bf16_fast_kernel<128, 128, 2, 2, false, false, EPI_SWIGLU>(GemmParams);
+#define MS_INST_EPI(EPI)                                                                                      \
+    template __global__ void gemm_bf16_fast_kernel<256, 256, 2, 4, false, false, EPI, false>(GemmParams);    \
+    template __global__ void gemm_bf16_fast_kernel<256, 256, 2, 4, false, false, EPI, true>(GemmParams);     \
+    template __global__ void gemm_bf16_fast_kernel<128, 128, 2, 2, false, false, EPI, false>(GemmParams);    \
+    template __global__ void gemm_bf16_fast_kernel<128, 128, 2, 2, false, false, EPI, true>(GemmParams)
+MS_INST_EPI(EPI_KD_DZ); MS_INST_EPI(EPI_KD_STATS); MS_INST_EPI(EPI_SWIGLU);
+#undef MS_INST_EPI
+
+// Kernel selection switches (measurements and tests): the environment gives the process-wide setting
+// (MS_GEMM_TILE = 128 / 256 forces the fast kernels' tile, -1 disables them; MS_GEMM_MFMA16 = 0 selects
+// v_mfma_f32_32x32x16_bf16), ms_k_gemm_config overrides it at run time.
+constexpr int kUnset = -1000;
+int g_tile_override = kUnset, g_mfma16_override = kUnset;
+int forced_tile() {
+    static const int env = [] { const char *e = getenv("MS_GEMM_TILE"); return e ? atoi(e) : 0; }();
+    return g_tile_override != kUnset ? g_tile_override : env;
+}
+bool use_mfma16() {
+    static const bool env = [] { const char *e = getenv("MS_GEMM_MFMA16"); return !e || atoi(e) != 0; }();
+    return g_mfma16_override != kUnset ? g_mfma16_override != 0 : env;
+}
+
+template <int BM, int BN, int WM, int WN, int EPI>
+void launch_fast_epi(const GemmParams &p, dim3 grid, hipStream_t s) {
+    // (the 128 x 128 dz variant would need more than the 256 registers that let two workgroups share a CU)
+    if (use_mfma16() && !(BM == 128 && EPI == EPI_KD_DZ))
+        gemm_bf16_fast_kernel<BM, BN, WM, WN, false, false, EPI, true><<<grid, 64 * WM * WN, 0, s>>>(p);
+    else gemm_bf16_fast_kernel<BM, BN, WM, WN, false, false, EPI, false><<<grid, 64 * WM * WN, 0, s>>>(p);
+}
 
 template <int BM, int BN, int WM, int WN>
 ms_status launch_bf16_fast(const GemmParams &p, int ta, int tb, int splits, hipStream_t s) {
     dim3 grid(p.tiles_m * p.tiles_n, splits);
     ProfScope ps((ta || tb) ? 1 : 0, 2.0 * p.M * p.N * p.K, s);
-#define GO(TA, TB) gemm_bf16_fast_kernel<BM, BN, WM, WN, TA, TB><<<grid, 64 * WM * WN, 0, s>>>(p)
+#define GO(TA, TB)                                                                                             \
+    do {                                                                                                       \
+        if (use_mfma16()) gemm_bf16_fast_kernel<BM, BN, WM, WN, TA, TB, EPI_NONE, true><<<grid, 64 * WM * WN, 0, s>>>(p);   \
+        else gemm_bf16_fast_kernel<BM, BN, WM, WN, TA, TB, EPI_NONE, false><<<grid, 64 * WM * WN, 0, s>>>(p);  \
+    } while (0)
     if (!ta && !tb) GO(false, false);
     else if (!ta && tb) GO(false, true);
     else if (ta && !tb) GO(true, false);
@@ -749,6 +895,14 @@ ms_status launch_bf16(const GemmParams &p, int ta, int tb, int splits, hipStream
 
 }  // namespace
 
+extern "C" ms_status ms_k_gemm_config(int32_t tile, int32_t mfma16) {
+    if (!(tile == -1 || tile == 0 || tile == 128 || tile == 256) || mfma16 < -1 || mfma16 > 1)
+        return ms_fail(MS_ERR_INVALID_ARG, "gemm_config: tile must be -1, 0, 128 or 256 and mfma16 -1, 0 or 1");
+    g_tile_override = tile == 0 ? kUnset : tile;
+    g_mfma16_override = mfma16 < 0 ? kUnset : mfma16;
+    return MS_OK;
+}
+
 extern "C" ms_status ms_k_gemm(int32_t dtype, int32_t trans_a, int32_t trans_b, int32_t M, int32_t N, int32_t K,
                                float alpha, const void *A, int64_t lda, const void *B, int64_t ldb, void *C,
                                int64_t ldc, int32_t c_fp32, int32_t accumulate, const void *bias,
@@ -780,7 +934,7 @@ extern "C" ms_status ms_k_gemm(int32_t dtype, int32_t trans_a, int32_t trans_b, 
     p.c_fp32 = c_fp32; p.accumulate = accumulate; p.res_fp32 = residual_fp32;
     // fast path (direct-to-LDS loads, descriptor-addressed epilogue) needs full K tiles for a K-contiguous
     // operand and 32-bit byte offsets; tile 256 x 256 when that still gives every CU work, else 128 x 128
-    static const int forced = [] { const char *e = getenv("MS_GEMM_TILE"); return e ? atoi(e) : 0; }();
+    const int forced = forced_tile();
     const long lim = (1L << 32) - (1L << 20);
     const long rows_a = trans_a ? K : M, rows_b = trans_b ? K : N;
     const bool fast = forced >= 0 && ((trans_a && trans_b) || K % BK == 0) && (rows_a + 256) * lda * 2 < lim &&
@@ -838,7 +992,7 @@ bool gemm_kd_epilogue_supported(int M, int N, int K, const void *A, long lda, co
                                 long ldz, const void *dz, long lddz, int dz_fp32) {
     auto al = [](const void *q) { return ((uintptr_t)q & 15) == 0; };
     const long lim = (1L << 32) - (1L << 20);
-    static const int forced = [] { const char *e = getenv("MS_GEMM_TILE"); return e ? atoi(e) : 0; }();
+    const int forced = forced_tile();
     return forced >= 0 && M > 0 && N > 0 && K > 0 && K % BK == 0 && N % 4 == 0 && al(A) && al(B) && al(zt) && lda % 8 == 0 &&
            ldb % 8 == 0 && ldz % 4 == 0 && ((long)M + 256) * lda * 2 < lim && ((long)N + 256) * ldb * 2 < lim &&
            ((long)M + 256) * ldz * 4 < lim && (!dz || (al(dz) && lddz % 4 == 0 && ((long)M + 256) * lddz * (dz_fp32 ? 4 : 2) < lim));
@@ -856,7 +1010,7 @@ ms_status gemm_kd_epilogue(int mode, int M, int N, int K, const void *A, long ld
     p.A = A; p.B = B; p.C = dz; p.lda = lda; p.ldb = ldb; p.ldc = lddz; p.M = M; p.N = N; p.K = K; p.alpha = 1.f;
     p.c_fp32 = dz_fp32;
     p.kd_zt = zt; p.kd_ldz = ldz; p.kd_stats = stats; p.kd_part = part; p.kd_nparts = nparts; p.kd_inv_t = inv_t; p.kd_coef = coef;
-    static const int forced = [] { const char *e = getenv("MS_GEMM_TILE"); return e ? atoi(e) : 0; }();
+    const int forced = forced_tile();
     const long tiles256 = (long)ms_cdiv(M, 256) * ms_cdiv(N, 256), tiles128 = (long)ms_cdiv(M, 128) * ms_cdiv(N, 128);
     const double eff256 = (double)tiles256 / (double)(ms_cdiv(tiles256, 256) * 256L);
     const double eff128 = (double)tiles128 / (double)(ms_cdiv(tiles128, 512) * 512L);
@@ -867,11 +1021,11 @@ ms_status gemm_kd_epilogue(int mode, int M, int N, int K, const void *A, long ld
     dim3 grid(p.tiles_m * p.tiles_n, 1);
     ProfScope ps(0, 2.0 * M * N * K, s);
     if (big) {
-        if (mode == EPI_KD_DZ) gemm_bf16_fast_kernel<256, 256, 2, 4, false, false, EPI_KD_DZ><<<grid, 512, 0, s>>>(p);
-        else gemm_bf16_fast_kernel<256, 256, 2, 4, false, false, EPI_KD_STATS><<<grid, 512, 0, s>>>(p);
+        if (mode == EPI_KD_DZ) launch_fast_epi<256, 256, 2, 4, EPI_KD_DZ>(p, grid, s);
+        else launch_fast_epi<256, 256, 2, 4, EPI_KD_STATS>(p, grid, s);
     } else {
-        if (mode == EPI_KD_DZ) gemm_bf16_fast_kernel<128, 128, 2, 2, false, false, EPI_KD_DZ><<<grid, 256, 0, s>>>(p);
-        else gemm_bf16_fast_kernel<128, 128, 2, 2, false, false, EPI_KD_STATS><<<grid, 256, 0, s>>>(p);
+        if (mode == EPI_KD_DZ) launch_fast_epi<128, 128, 2, 2, EPI_KD_DZ>(p, grid, s);
+        else launch_fast_epi<128, 128, 2, 2, EPI_KD_STATS>(p, grid, s);
     }
     MS_LAUNCH_CHECK();
     return MS_OK;
@@ -884,7 +1038,7 @@ bool gemm_swiglu_supported(int M, int F, int K, const void *A, long lda, const v
                            const void *gate_up, long ldgu) {
     auto al = [](const void *q) { return ((uintptr_t)q & 15) == 0; };
     const long lim = (1L << 32) - (1L << 20);
-    static const int forced = [] { const char *e = getenv("MS_GEMM_TILE"); return e ? atoi(e) : 0; }();
+    const int forced = forced_tile();
     return forced >= 0 && M > 0 && F > 0 && K > 0 && K % BK == 0 && F % 4 == 0 && al(A) && al(W) && al(act) && lda % 8 == 0 &&
            ldw % 8 == 0 && ldact % 4 == 0 && ((long)M + 256) * lda * 2 < lim && (2L * F + 256) * ldw * 2 < lim &&
            ((long)M + 256) * ldact * 2 < lim && (!gate_up || (al(gate_up) && ldgu % 4 == 0 && ((long)M + 256) * ldgu * 2 < lim));
@@ -897,7 +1051,7 @@ ms_status gemm_swiglu(int M, int F, int K, const void *A, long lda, const void *
     GemmParams p = {};
     p.A = A; p.B = W; p.C = act; p.lda = lda; p.ldb = ldw; p.ldc = ldact; p.M = M; p.N = F; p.K = K; p.alpha = 1.f;
     p.sg_f = F; p.sg_gu = gate_up; p.sg_ldgu = ldgu;
-    static const int forced = [] { const char *e = getenv("MS_GEMM_TILE"); return e ? atoi(e) : 0; }();
+    const int forced = forced_tile();
     // a tile covers BN/2 output columns (BN weight rows: gate and up)
     const long tiles256 = (long)ms_cdiv(M, 256) * ms_cdiv(F, 128), tiles128 = (long)ms_cdiv(M, 128) * ms_cdiv(F, 64);
     const double eff256 = (double)tiles256 / (double)(ms_cdiv(tiles256, 256) * 256L);
@@ -908,8 +1062,8 @@ ms_status gemm_swiglu(int M, int F, int K, const void *A, long lda, const void *
     p.k_tiles_per_split = ms_cdiv(K, BK);
     dim3 grid(p.tiles_m * p.tiles_n, 1);
     ProfScope ps(0, 4.0 * M * F * K, s);
-    if (big) gemm_bf16_fast_kernel<256, 256, 2, 4, false, false, EPI_SWIGLU><<<grid, 512, 0, s>>>(p);
-    else gemm_bf16_fast_kernel<128, 128, 2, 2, false, false, EPI_SWIGLU><<<grid, 256, 0, s>>>(p);
+    if (big) launch_fast_epi<256, 256, 2, 4, EPI_SWIGLU>(p, grid, s);
+    else launch_fast_epi<128, 128, 2, 2, EPI_SWIGLU>(p, grid, s);
     MS_LAUNCH_CHECK();
     return MS_OK;
 }

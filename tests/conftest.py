@@ -13,6 +13,19 @@ def pytest_configure(config):
     config.addinivalue_line("markers", "gpu: needs a real MI355X (run with -m gpu)")
 
 
+# Kernel selections of the bf16 GEMMs that the shapes of the tests would not all reach by themselves: the
+# automatic choice, both workgroup tiles with both MFMA shapes, and the generic kernel.
+GEMM_CONFIGS = [(0, -1), (256, 1), (256, 0), (128, 1), (128, 0), (-1, -1)]
+
+
+@pytest.fixture(params=GEMM_CONFIGS, ids=lambda c: f"tile{c[0]}_mfma{c[1]}")
+def gemm_config(request):
+    from paper_2605_10501_amd import binding as B
+    B.k_gemm_config(*request.param)
+    yield request.param
+    B.k_gemm_config(0, -1)
+
+
 @pytest.fixture
 def rng():
     return np.random.default_rng(1234)

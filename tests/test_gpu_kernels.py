@@ -37,7 +37,7 @@ def _gemm_cases():
 
 
 @pytest.mark.parametrize("ta,tb,M,N,K", _gemm_cases())
-def test_gemm_bf16_all_layouts(ta, tb, M, N, K):
+def test_gemm_bf16_all_layouts(ta, tb, M, N, K, gemm_config):
     a = dev(f"a{M}{K}", (K, M) if ta else (M, K), torch.bfloat16)
     b = dev(f"b{N}{K}", (K, N) if tb else (N, K), torch.bfloat16)
     ref = (f64(a).T if ta else f64(a)) @ (f64(b) if tb else f64(b).T)
@@ -45,7 +45,7 @@ def test_gemm_bf16_all_layouts(ta, tb, M, N, K):
     assert_parity(B.k_gemm(a, b, ta, tb), round_bf16(ref), TOL_BF16, "bf16 out")
 
 
-def test_gemm_epilogues_and_split_k():
+def test_gemm_epilogues_and_split_k(gemm_config):
     M, N, K = 400, 264, 4096
     a, b = dev("ea", (M, K), torch.bfloat16), dev("eb", (N, K), torch.bfloat16, 0.05)
     bias, res = dev("ebias", (N,), torch.bfloat16), dev("eres", (M, N), torch.bfloat16)

@@ -93,7 +93,7 @@ def small_c2(seed):
     return w
 
 
-def test_c2_reduced_bf16_distill_step():
+def test_c2_reduced_bf16_distill_step(gemm_config):
     run_distill(small_c2(0), 0, tol=TOL_BF16, tol_loss=TOL_LOSS_BF16, tol_wgrad=TOL_BF16)
 
 
@@ -152,12 +152,7 @@ def test_skipped_section_is_a_noop():
     assert all(float(t.abs().max()) == 0.0 for t in grads["layers"][0].values())
 
 
-@pytest.mark.parametrize("dtype,vocab,chunk,n,ht,hs,T,token_block", [
-    ("bf16", 5000, 1024, 700, 512, 256, 2.0, 0), ("bf16", 2048, 2048, 130, 136, 72, 1.0, 0), ("fp32", 1000, 256, 97, 64, 32, 1.5, 0),
-    # the variant that keeps a token block's teacher logits between the passes: three ragged blocks, one block
-    # larger than the batch, and the unfused fp32 path
-    ("bf16", 5000, 1024, 700, 512, 256, 2.0, 256), ("bf16", 5000, 1024, 700, 512, 256, 2.0, 4096), ("fp32", 1000, 256, 97, 64, 32, 1.5, 40)])
-def test_kd_loss_standalone(dtype, vocab, chunk, n, ht, hs, T, token_block):
+def _kd_loss_standalone(dtype, vocab, chunk, n, ht, hs, T, token_block):
     kd = wl.KDConfig(vocab, ht, hs, T, chunk, dtype, token_block)
     dt = torch.bfloat16 if dtype == "bf16" else torch.float32
     rnd = round_bf16 if dtype == "bf16" else identity
@@ -176,3 +171,17 @@ def test_kd_loss_standalone(dtype, vocab, chunk, n, ht, hs, T, token_block):
     same = B.kd_loss_forward_backward(wl.scaled(kd, h_teacher=hs), ws, ws, h_s, h_s)
     assert abs(same["loss"].item()) < 1e-5 and float(same["d_h_s"].abs().max()) < 1e-6      # KL = 0 for equal logits
     assert float(out["kl_tok"].min()) >= 0.0
+
+
+# the variant that keeps a token block's teacher logits between the passes (token_block > 0): three ragged blocks and
+# one block larger than the batch
+@pytest.mark.parametrize("vocab,chunk,n,ht,hs,T,token_block", [
+    (5000, 1024, 700, 512, 256, 2.0, 0), (2048, 2048, 130, 136, 72, 1.0, 0), (5000, 1024, 700, 512, 256, 2.0, 256),
+    (5000, 1024, 700, 512, 256, 2.0, 4096)])
+def test_kd_loss_standalone(vocab, chunk, n, ht, hs, T, token_block, gemm_config):
+    _kd_loss_standalone("bf16", vocab, chunk, n, ht, hs, T, token_block)
+
+
+@pytest.mark.parametrize("token_block", [0, 40])
+def test_kd_loss_standalone_fp32(token_block):
+    _kd_loss_standalone("fp32", 1000, 256, 97, 64, 32, 1.5, token_block)
