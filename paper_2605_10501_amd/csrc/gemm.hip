@@ -270,9 +270,12 @@ __device__ __forceinline__ void sched_pairs(std::integer_sequence<int, I...>) {
 }
 // Scheduling pattern of one k-step with 16-row fragments: per row block, its NB MFMAs and then the reads that
 // refill its A fragment (RA reads) and, behind the first NB row blocks, one B fragment (RB reads).
-template <int NB, int RA, int RB, int... I>
+// VM = number of direct-to-LDS loads issued in this k-step (0, or one tile's worth): spread evenly over the row blocks.
+template <int NB, int RA, int RB, int VM, int... I>
 __device__ __forceinline__ void sched_mfma_then_reads(std::integer_sequence<int, I...>) {
-    ((__builtin_amdgcn_sched_group_barrier(0x008, NB, 0), __builtin_amdgcn_sched_group_barrier(0x100, RA + (I < NB ? RB : 0), 0)), ...);
+    constexpr int MB = sizeof...(I), PB = (VM + MB - 1) / MB;      // loads per row block
+    ((__builtin_amdgcn_sched_group_barrier(0x008, NB, 0), __builtin_amdgcn_sched_group_barrier(0x100, RA + (I < NB ? RB : 0), 0),
+      (I * PB < VM ? __builtin_amdgcn_sched_group_barrier(0x020, (VM - I * PB < PB ? VM - I * PB : PB), 0) : (void)0)), ...);
 }
 template <int R, int M>
 __device__ __forceinline__ void interleave_reads_with_mfma() {
@@ -450,8 +453,9 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_bf16_fast_kernel(GemmParams
     // fragments there are twice as many fragment registers per k-step, so the A fragment of row block i is
     // read right after the MFMAs of row block i, into the registers those MFMAs have just released; only the
     // B fragments are held twice.
-    auto step = [&](auto cur_c, const bf16_t *la, const bf16_t *lb, int lkk) __attribute__((always_inline)) {
+    auto step = [&](auto cur_c, auto fetch_c, const bf16_t *la, const bf16_t *lb, int lkk) __attribute__((always_inline)) {
         constexpr int cur = decltype(cur_c)::value;          // compile-time: the fragment arrays must stay registers
+        constexpr int VM = decltype(fetch_c)::value ? (BM + BN) / 8 / (WM * WN) : 0;   // loads of a fetch issued just before
         if constexpr (M16) {
             static_assert(NI <= MI, "B fragments are read behind the first NI row blocks");
 #pragma unroll
@@ -462,7 +466,7 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_bf16_fast_kernel(GemmParams
                 load_a(la, lkk, cur ^ 1, i);
                 if (i < NI) load_b(lb, lkk, cur ^ 1, i);
             }
-            sched_mfma_then_reads<NI, (TA ? 2 : 1), (TB ? 2 : 1)>(std::make_integer_sequence<int, MI>{});
+            sched_mfma_then_reads<NI, (TA ? 2 : 1), (TB ? 2 : 1), VM>(std::make_integer_sequence<int, MI>{});
         } else {
             load_frags(la, lb, lkk, cur ^ 1);
             mfma_step(cur);
@@ -479,14 +483,14 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_bf16_fast_kernel(GemmParams
         using S0 = std::integral_constant<int, 0>;
         using S1 = std::integral_constant<int, 1>;
         static_assert(KS == 2 || KS == 4, "k-steps per K tile");
-        step(S0{}, ca, cb, 1);
+        step(S0{}, S0{}, ca, cb, 1);
         if constexpr (KS == 4) {
-            step(S1{}, ca, cb, 2);
-            step(S0{}, ca, cb, 3);
+            step(S1{}, S0{}, ca, cb, 2);
+            step(S0{}, S0{}, ca, cb, 3);
         }
         __syncthreads();
         fetch(kt_fetch, fa, fb);
-        step(S1{}, na, nb, 0);
+        step(S1{}, S1{}, na, nb, 0);
     };
 
     fetch(0, As0, Bs0);
