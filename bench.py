@@ -177,7 +177,7 @@ def main():
     torch.cuda.synchronize()
     prof = B.profile_read()
     B.profile_enable(0)
-    sweep, adamw, probe_tflops, probe_rand_tflops, copy_gbs, variant = [], None, None, None, None, None
+    sweep, adamw, probe_tflops, probe_rand_tflops, probe16_rand_tflops, copy_gbs, variant = [], None, None, None, None, None, None
     clocks = {}
     side = torch.cuda.Stream()
     clk = torch.zeros(2, dtype=torch.int64, device=dev)
@@ -239,6 +239,11 @@ def main():
         clocks["mfma_register_loop"] = clock_during(lambda: B.k_mfma_probe(512, 10000, sink), 4, int(3e6 * sec_probe))
         clocks["mfma_register_loop_random_operands"] = clock_during(
             lambda: B.k_mfma_probe(512, 10000, sink, random_operands=True), 4, int(3e6 * sec_probe_r))
+        # the 16x16x32 shape the GEMMs use, on random operands
+        sec_probe_16, _ = timed(lambda: B.k_mfma_probe(512, 10000, sink, random_operands=True, mfma16=True), 3)
+        probe16_rand_tflops = 512 * 8 * 10000 * 8 * 32768 / sec_probe_16 / 1e12
+        clocks["mfma16_register_loop_random_operands"] = clock_during(
+            lambda: B.k_mfma_probe(512, 10000, sink, random_operands=True, mfma16=True), 4, int(3e6 * sec_probe_16))
         clocks["whole_step"] = clock_during(step, 3, int(2e6 * sec_step))
         src = torch.ones(1 << 30, dtype=torch.uint8, device=dev)
         dst = torch.empty_like(src)
@@ -284,6 +289,7 @@ def main():
         "variant_cached_teacher_logits": variant, "teacher_microbatch_sweep": sweep, "student_adamw_step": adamw,
         "measured_references": None if args.step_only else {"mfma_register_loop_tflops": probe_tflops,
                                                              "mfma_register_loop_random_operands_tflops": probe_rand_tflops,
+                                                             "mfma16_register_loop_random_operands_tflops": probe16_rand_tflops,
                                                              "shader_clock_mhz": clocks,
                                                              "copy_1gib_read_plus_write_gbs": copy_gbs},
         "roofline": {"kernel": "gemm_bf16_fast_kernel (A[M,K] B[N,K]^T, all forward linears and lm_head chunks)",

@@ -119,12 +119,14 @@ ms_status ms_k_copy(const void *src, void *dst, size_t bytes, void *stream);
 
 /* Register-resident bf16 MFMA loop on every CU (no memory traffic in the loop): the matrix-core rate the chip
  * sustains at its clocks under load, as a reference beside the published peak.  Each of `workgroups` x 8 waves
- * issues iters x 8 independent v_mfma_f32_32x32x16_bf16; sink_dev (>= workgroups * 512 floats) receives one value
+ * issues iters x 8 independent v_mfma_f32_32x32x16_bf16 (mfma16 = 0) or iters x 16 independent
+ * v_mfma_f32_16x16x32_bf16 (mfma16 = 1: the same flops); sink_dev (>= workgroups * 512 floats) receives one value
  * per lane so that the loop is not removed.  Algorithmic flops = workgroups * 8 * iters * 8 * 32768.
  * random_operands = 0: small constants in the operand registers (lowest bit activity); 1: pseudo-random signs
  * and mantissas with magnitudes 2^-4 .. 2^4, as real weights and activations have.  The chip's power management
  * lowers the clock under the second, so the two rates bracket what a bf16 kernel can reach on real data. */
-ms_status ms_k_mfma_probe(int32_t workgroups, int32_t iters, int32_t random_operands, float *sink_dev, void *stream);
+ms_status ms_k_mfma_probe(int32_t workgroups, int32_t iters, int32_t random_operands, int32_t mfma16, float *sink_dev,
+                          void *stream);
 
 /* Clock monitor: one wave that runs for about `microseconds` (1 .. 1000000; bounded by a poll count as well) and
  * writes to out_dev[0] the shader-clock cycles and to out_dev[1] the ticks of the constant 100 MHz counter that

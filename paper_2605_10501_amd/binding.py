@@ -411,8 +411,8 @@ def k_attention_backward(qkv, o, lse, d_o, batch, n_q_heads, n_kv_heads, head_di
     return dqkv
 
 
-def k_mfma_probe(workgroups, iters, sink, random_operands=False):
-    _check(lib().ms_k_mfma_probe(workgroups, iters, int(random_operands), _p(sink), _stream()))
+def k_mfma_probe(workgroups, iters, sink, random_operands=False, mfma16=False):
+    _check(lib().ms_k_mfma_probe(workgroups, iters, int(random_operands), int(mfma16), _p(sink), _stream()))
 
 
 def k_clock_monitor(microseconds, out):

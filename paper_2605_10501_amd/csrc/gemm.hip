@@ -1074,12 +1074,15 @@ ms_status gemm_swiglu(int M, int F, int K, const void *A, long lda, const void *
 
 // ------------------------------------------------------------------ matrix-core rate probe
 namespace {
+template <bool M16>
 __global__ __launch_bounds__(512) void mfma_probe_kernel(int iters, int random_operands, float *sink) {
-    f32x16 acc[8];
+    // the same flops per iteration for both shapes: 8 x 32x32x16 or 16 x 16x16x32, all independent
+    constexpr int NACC = M16 ? 16 : 8, ACC_N = M16 ? 4 : 16;
+    std::conditional_t<M16, f32x4, f32x16> acc[NACC];
 #pragma unroll
-    for (int i = 0; i < 8; ++i)
+    for (int i = 0; i < NACC; ++i)
 #pragma unroll
-        for (int r = 0; r < 16; ++r) acc[i][r] = 0.f;
+        for (int r = 0; r < ACC_N; ++r) acc[i][r] = 0.f;
     bf16x8 a, b;
 #pragma unroll
     for (int e = 0; e < 8; ++e) { a[e] = (bf16_t)(float)(threadIdx.x & 3); b[e] = (bf16_t)(1.f / 64.f); }
@@ -1098,13 +1101,16 @@ __global__ __launch_bounds__(512) void mfma_probe_kernel(int iters, int random_o
     }
     for (int it = 0; it < iters; ++it) {
 #pragma unroll
-        for (int i = 0; i < 8; ++i) acc[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, acc[i], 0, 0, 0);
+        for (int i = 0; i < NACC; ++i) {
+            if constexpr (M16) acc[i] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b, acc[i], 0, 0, 0);
+            else acc[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, acc[i], 0, 0, 0);
+        }
     }
     float t = 0.f;
 #pragma unroll
-    for (int i = 0; i < 8; ++i)
+    for (int i = 0; i < NACC; ++i)
 #pragma unroll
-        for (int r = 0; r < 16; ++r) t += acc[i][r];
+        for (int r = 0; r < ACC_N; ++r) t += acc[i][r];
     sink[(long)blockIdx.x * 512 + threadIdx.x] = t;
 }
 
@@ -1132,9 +1138,11 @@ extern "C" ms_status ms_k_clock_monitor(int32_t microseconds, int64_t *out_dev, 
     return MS_OK;
 }
 
-extern "C" ms_status ms_k_mfma_probe(int32_t workgroups, int32_t iters, int32_t random_operands, float *sink_dev, void *stream) {
+extern "C" ms_status ms_k_mfma_probe(int32_t workgroups, int32_t iters, int32_t random_operands, int32_t mfma16, float *sink_dev,
+                                     void *stream) {
     if (workgroups <= 0 || iters <= 0 || !sink_dev) return ms_fail(MS_ERR_INVALID_ARG, "mfma_probe: bad argument");
-    mfma_probe_kernel<<<workgroups, 512, 0, (hipStream_t)stream>>>(iters, random_operands, sink_dev);
+    if (mfma16) mfma_probe_kernel<true><<<workgroups, 512, 0, (hipStream_t)stream>>>(iters, random_operands, sink_dev);
+    else mfma_probe_kernel<false><<<workgroups, 512, 0, (hipStream_t)stream>>>(iters, random_operands, sink_dev);
     MS_LAUNCH_CHECK();
     return MS_OK;
 }

@@ -212,9 +212,11 @@ def test_attention_forward_backward(dtype, causal, nq, nkv, hd, cu, sharp):
 def test_mfma_probe_counts_what_it_claims():
     # every accumulator element gains (row % 4) / 4 per MFMA; a lane's 16 rows cover each residue 4 times
     sink = torch.zeros(4 * 512, dtype=torch.float32, device="cuda")
-    B.k_mfma_probe(4, 10, sink)
-    torch.cuda.synchronize()
-    assert torch.all(sink == 480.0)
+    for mfma16 in (False, True):      # 16x16x32: (row % 4) / 2 per MFMA, 4 rows per accumulator, 16 MFMAs per iteration
+        sink.zero_()
+        B.k_mfma_probe(4, 10, sink, mfma16=mfma16)
+        torch.cuda.synchronize()
+        assert torch.all(sink == 480.0), mfma16
     # random operands: same instruction stream, data-dependent values; finite and reproducible
     B.k_mfma_probe(4, 10, sink, random_operands=True)
     first = sink.clone()
