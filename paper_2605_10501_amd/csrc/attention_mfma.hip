@@ -88,17 +88,30 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
     const int q = q0 + lrow;
 
     auto compute = [&](int j, const bf16_t *kt, const bf16_t *vt) {
-        // S^T[key][q] for the 64 keys of the tile: two 32-key blocks
+        // S^T[key][q] for the 64 keys of the tile: two 32-key blocks (two independent accumulation chains); the
+        // K fragments of k-step ks + 1 are read while the MFMAs of k-step ks run
         f32x16 st[2];
 #pragma unroll
-        for (int kb = 0; kb < 2; ++kb) {
+        for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
             for (int r = 0; r < 16; ++r) st[kb][r] = 0.f;
+        auto kfrag = [&](int ks, int kb) {
+            return *(const bf16x8 *)(kt + (ks / 4) * 4096 + lds_off(kb * 32 + lrow, (ks % 4) * 2 + half));
+        };
+        bf16x8 kf[2][2];
+        kf[0][0] = kfrag(0, 0);
+        kf[0][1] = kfrag(0, 1);
+        __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
 #pragma unroll
-            for (int ks = 0; ks < D::KST; ++ks) {
-                const bf16x8 kf = *(const bf16x8 *)(kt + (ks / 4) * 4096 + lds_off(kb * 32 + lrow, (ks % 4) * 2 + half));
-                st[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[ks], st[kb], 0, 0, 0);
+        for (int ks = 0; ks < D::KST; ++ks) {
+            if (ks + 1 < D::KST) {
+                kf[(ks + 1) & 1][0] = kfrag(ks + 1, 0);
+                kf[(ks + 1) & 1][1] = kfrag(ks + 1, 1);
             }
+            st[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[ks & 1][0], qf[ks], st[0], 0, 0, 0);
+            st[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[ks & 1][1], qf[ks], st[1], 0, 0, 0);
+            __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
+            __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);
         }
         // mask (only tiles that touch the diagonal or the end of the sequence: wave-uniform test), row
         // maximum on the raw scores (one query per lane; the other half-wave holds the other keys),
