@@ -71,6 +71,8 @@ def test_probe_arguments_are_checked_before_any_launch():
     assert lib.ms_k_clock_monitor(0, C.c_void_p(256), None) == -1
     assert lib.ms_k_clock_monitor(2_000_000, C.c_void_p(256), None) == -1        # longer than a second
     assert lib.ms_k_clock_monitor(100, None, None) == -1 and b"clock_monitor" in lib.ms_last_error()
+    assert lib.ms_k_gemm_config(64, -1) == -1 and lib.ms_k_gemm_config(0, 2) == -1 and b"gemm_config" in lib.ms_last_error()
+    assert lib.ms_k_gemm_config(256, 1) == 0 and lib.ms_k_gemm_config(0, -1) == 0
     assert lib.ms_k_mfma_probe(0, 10, 0, 0, C.c_void_p(256), None) == -1
     assert lib.ms_k_mfma_probe(4, 10, 1, 1, None, None) == -1
 
