@@ -40,6 +40,14 @@ ms_status ms_k_gemm(int32_t dtype, int32_t trans_a, int32_t trans_b, int32_t M, 
                     int64_t ldc, int32_t c_fp32, int32_t accumulate, const void *bias,
                     const void *residual, int64_t ldr, int32_t residual_fp32, int32_t split_k, void *stream);
 
+/* Gate/up projection of a SwiGLU FFN with the activation fused into the GEMM (bf16 only):
+ *   gate_up[M, 2F] = round(A[M,K] W[2F,K]^T)  (W rows: F gate rows, then F up rows; written if gate_up != NULL)
+ *   act[M, F]      = silu(gate) * up, evaluated on the rounded pre-activations (what a separate kernel would read).
+ * Needs K % 64 == 0, F % 4 == 0, 16-byte aligned rows; MS_ERR_UNSUPPORTED otherwise (the caller then runs
+ * ms_k_gemm + ms_k_act_forward). */
+ms_status ms_k_gemm_swiglu(int32_t M, int32_t F, int32_t K, const void *A, int64_t lda, const void *W, int64_t ldw,
+                           void *act, int64_t ldact, void *gate_up, int64_t ldgu, void *stream);
+
 /* kind 0: RMSNorm y = x rstd g; kind 1: LayerNorm y = (x - mean) rstd g + b.
  * mean (kind 1 only) and rstd are fp32 [n] outputs kept for the backward pass.
  * x_fp32 != 0: x is fp32 although dtype is bf16 (g, b, y stay bf16). */

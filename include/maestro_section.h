@@ -156,6 +156,21 @@ ms_status ms_kd_loss_forward_backward(const ms_kd_config *kd, int32_t n_tokens,
                                       void *d_h_student, void *d_w_student,
                                       void *workspace_dev, size_t workspace_bytes, void *stream);
 
+/* The same computation for callers that cannot allocate device memory or pass a workspace: code under HIP graph
+ * capture, tight serving / evaluation loops, harnesses that forbid hipMalloc.  The scratch that the call above takes
+ * from the caller's workspace (chunk logits, per-token statistics, the logit gradient, the fp32 d_h_student
+ * accumulator) lives in a fixed device array inside the library instead: MS_KD_STATIC_SCRATCH_BYTES per GPU, held from
+ * the library's first use on that GPU until the process ends.  The call allocates and frees nothing (with
+ * ms_profile_enable(1) the launchers create HIP events: leave profiling off here).  A call whose
+ * ms_kd_workspace_bytes(kd, n_tokens) exceeds MS_KD_STATIC_SCRATCH_BYTES is rejected with MS_ERR_WORKSPACE before
+ * anything is launched (examples that fit: 1024 tokens with chunk 4096 and h_student 2048; 4096 tokens with chunk 1024).
+ * All calls on one GPU share the one array: calls that overlap in time on a GPU (different streams or threads) race;
+ * calls on one stream are ordered and each clears what it needs.  Results are those of ms_kd_loss_forward_backward. */
+#define MS_KD_STATIC_SCRATCH_BYTES (64u << 20)
+ms_status ms_kd_loss_forward_backward_static(const ms_kd_config *kd, int32_t n_tokens, const void *h_teacher,
+                                             const void *h_student, float *loss_dev, float *kl_per_token_dev,
+                                             void *d_h_student, void *d_w_student, void *stream);
+
 /* Vision -> language hand-off (Sec. 2.1 and Sec. 4.1: the encoder's visual tokens are down-sampled 4:1 along the
  * sequence and joined with the text tokens to form the LLM's input; the operator itself is a reading: patch
  * merger + MLP projector).  Group g = visual tokens merge*g .. merge*g + merge-1 of the packed encoder output

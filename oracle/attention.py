@@ -9,6 +9,8 @@ re-associate.
 """
 import numpy as np
 
+from .rounding import identity
+
 
 def _softmax_rows(s):
     m = np.max(s, axis=1, keepdims=True)
@@ -49,7 +51,7 @@ def attention_fwd(q, k, v, cu_seqlens, causal, return_lse=False):
     return (o, lse) if return_lse else o
 
 
-def attention_bwd(do, q, k, v, cu_seqlens, causal, o=None):
+def attention_bwd(do, q, k, v, cu_seqlens, causal, o=None, rnd_p=identity):
     """Gradients of attention_fwd: dV = P^T dO, dP = dO V^T,
     dS = P * (dP - delta), dQ = dS K / sqrt(hd), dK = dS^T Q / sqrt(hd);
     dK and dV are summed over the query heads that share a KV head.
@@ -57,7 +59,13 @@ def attention_bwd(do, q, k, v, cu_seqlens, causal, o=None):
     delta is the softmax-Jacobian row term rowsum(dP * P).  Because O = P V it also equals
     rowsum(dO * O); when the stored forward output `o` is passed (the backward pass of a
     section reads the output tensor the forward pass stored, rounded under the bf16
-    contract) that second form is used, otherwise the first."""
+    contract) that second form is used, otherwise the first.
+
+    `rnd_p` is the materialisation rounding of the two score-shaped matrices that enter a
+    matrix product as an operand: P in dV = P^T dO, and dS in dQ = dS K and dK = dS^T Q.  A
+    path whose matrix units take bf16 operands ("bf16 activations with fp32 accumulation")
+    rounds exactly these two; the probabilities inside dS = P * (dP - delta), dP and delta
+    stay unrounded.  identity (the default) is the plain definition."""
     n, nq, hd = q.shape
     nkv = k.shape[1]
     grp = nq // nkv
@@ -74,13 +82,13 @@ def attention_bwd(do, q, k, v, cu_seqlens, causal, o=None):
             g = h // grp
             p = _probs(q[s0:s1, h], k[s0:s1, g], causal)
             doh = do[s0:s1, h]
-            dv[s0:s1, g] += p.T @ doh
+            dv[s0:s1, g] += rnd_p(p).T @ doh
             dp = doh @ v[s0:s1, g].T
             if o is None:
                 delta = np.sum(dp * p, axis=1, keepdims=True)
             else:
                 delta = np.sum(doh * o[s0:s1, h], axis=1, keepdims=True)
-            ds = p * (dp - delta)
+            ds = rnd_p(p * (dp - delta))
             dq[s0:s1, h] = (ds @ k[s0:s1, g]) * scale
             dk[s0:s1, g] += (ds.T @ q[s0:s1, h]) * scale
     return dq, dk, dv

@@ -14,8 +14,10 @@ hidden states, never logits, cross a section boundary: Sec. 3.1).
 `rnd` is applied exactly where the bf16 HIP path stores a tensor between
 kernels; `rnd_res` (default: the same as `rnd`) is applied to the residual
 stream (layer inputs / outputs and the post-attention sum), which a path may
-keep in higher precision than the other activations.  With `rnd=identity`
-everything is plain float64.
+keep in higher precision than the other activations.  In the backward pass
+`rnd` is also the rounding of the attention probabilities and score gradients
+where they enter a matrix product as operands (attention_bwd's `rnd_p`).  With
+`rnd=identity` everything is plain float64.
 """
 from dataclasses import dataclass
 
@@ -122,7 +124,7 @@ def section_backward(spec, weights, cu_seqlens, cache, d_h_out, rnd=identity, rn
         do, g["w_o"], g["b_o"] = ops.linear_bwd(dx2, c["o"], lw["w_o"], bias)
         do = rnd(do).reshape(n, nq, hd)
         dq, dk, dv = attention_bwd(do, c["q"], c["k"], c["v"], cu_seqlens, causal=dec,
-                                   o=c["o"].reshape(n, nq, hd))
+                                   o=c["o"].reshape(n, nq, hd), rnd_p=rnd)
         dq, dk, dv = rnd(dq), rnd(dk), rnd(dv)
         if dec:
             dq = rnd(ops.rope_apply(dq, cache["pos"], spec.rope_base, inverse=True))

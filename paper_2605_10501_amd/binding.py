@@ -202,6 +202,18 @@ def kd_loss_forward_backward(kd, w_teacher, w_student, h_teacher, h_student, los
     return dict(loss=loss, kl_tok=kl, d_h_s=d_h)
 
 
+KD_STATIC_SCRATCH_BYTES = 64 << 20
+
+
+def kd_loss_forward_backward_static(kd, w_teacher, w_student, h_teacher, h_student, loss, kl_tok, d_h_student,
+                                    d_w_student=None, loss_scale=None):
+    """The allocation-free variant: every output is the caller's tensor, the scratch is the library's built-in array."""
+    n = h_student.shape[0]
+    kdc = _kd_c(kd, w_teacher, w_student, (1.0 / max(n, 1)) if loss_scale is None else loss_scale)
+    _check(lib().ms_kd_loss_forward_backward_static(C.byref(kdc), n, _p(h_teacher), _p(h_student), _p(loss), _p(kl_tok),
+                                                    _p(d_h_student), _p(d_w_student), _stream()))
+
+
 def pack_microbatches(lengths, token_budget, policy=0):
     """Returns (order, mb_offsets, cu_seqlens_per_mb) as Python lists."""
     n = len(lengths)
@@ -310,6 +322,17 @@ def k_gemm(a, b, trans_a=False, trans_b=False, c=None, c_fp32=False, accumulate=
                            _p(bias), _p(residual), C.c_int64(residual.stride(0) if residual is not None else 0),
                            int(res_fp32), split_k, _stream()))
     return c
+
+
+def k_gemm_swiglu(a, w, want_gate_up=True):
+    """a[M,K], w[2F,K] (gate rows | up rows) -> (act[M,F], gate_up[M,2F] or None); bf16."""
+    M, K = a.shape
+    F = w.shape[0] // 2
+    act = torch.empty((M, F), dtype=a.dtype, device=a.device)
+    gu = torch.empty((M, 2 * F), dtype=a.dtype, device=a.device) if want_gate_up else None
+    _check(lib().ms_k_gemm_swiglu(M, F, K, _p(a), C.c_int64(a.stride(0)), _p(w), C.c_int64(w.stride(0)), _p(act),
+                                  C.c_int64(F), _p(gu), C.c_int64(2 * F), _stream()))
+    return act, gu
 
 
 def k_norm_forward(kind, x, g, b, eps):

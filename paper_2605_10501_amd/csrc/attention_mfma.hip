@@ -170,14 +170,14 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
     };
 
     issue(0, K0, V0);
-    __syncthreads();
+    dma_publish_barrier();
     for (int j = 0; j < nkt; j += 2) {
         if (j + 1 < nkt) issue(j + 1, K1, V1);
         compute(j, K0, V0);
-        __syncthreads();
+        dma_publish_barrier();
         if (j + 2 < nkt) issue(j + 2, K0, V0);
         if (j + 1 < nkt) compute(j + 1, K1, V1);
-        __syncthreads();
+        dma_publish_barrier();
     }
 
     l += __shfl_xor(l, 32, 64);
@@ -329,14 +329,14 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
     };
 
     issue(0, K0, V0);
-    __syncthreads();
+    dma_publish_barrier();
     for (int j = 0; j < nkt; j += 2) {
         if (j + 1 < nkt) issue(j + 1, K1, V1);
         compute(j, K0, V0);
-        __syncthreads();
+        dma_publish_barrier();
         if (j + 2 < nkt) issue(j + 2, K0, V0);
         if (j + 1 < nkt) compute(j + 1, K1, V1);
-        __syncthreads();
+        dma_publish_barrier();
     }
     if (!qok) return;
     bf16_t *op = dqkv + (long)q * ld + (long)h * HD;
@@ -526,14 +526,14 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
                 if constexpr (ONE_PASS) acc2[i][r] = 0.f;
             }
         issue(0, Q0, O0, F0);
-        __syncthreads();
+        dma_publish_barrier();
         for (int it = 0; it < niter; it += 2) {
             if (it + 1 < niter) issue(it + 1, Q1, O1, F1);
             compute(which, it, Q0, O0, F0);
-            __syncthreads();
+            dma_publish_barrier();
             if (it + 2 < niter) issue(it + 2, Q0, O0, F0);
             if (it + 1 < niter) compute(which, it + 1, Q1, O1, F1);
-            __syncthreads();
+            dma_publish_barrier();
         }
     };
     if constexpr (ONE_PASS) {

@@ -495,13 +495,13 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_bf16_fast_kernel(GemmParams
             step(S1{}, S0{}, ca, cb, 2);
             step(S0{}, S0{}, ca, cb, 3);
         }
-        __syncthreads();
+        dma_publish_barrier();
         fetch(kt_fetch, fa, fb);
         step(S1{}, S1{}, na, nb, 0);
     };
 
     fetch(0, As0, Bs0);
-    __syncthreads();
+    dma_publish_barrier();
     fetch(1, As1, Bs1);
     load_frags(As0, Bs0, 0, 0);
     // two K tiles per trip so that each half names its LDS buffers statically; an odd tile count is
@@ -510,7 +510,7 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_bf16_fast_kernel(GemmParams
         tile(As0, Bs0, As1, Bs1, As0, Bs0, kt + 2);
         tile(As1, Bs1, As0, Bs0, As1, Bs1, kt + 3);
     }
-    __syncthreads();   // the (all-zero) tiles still in flight must land before the epilogue reuses LDS
+    dma_publish_barrier();   // the (all-zero) tiles still in flight must land before the epilogue reuses LDS
 
     // ---- epilogue staging: the accumulators of the wave's 32-row block i go to LDS as [32 rows][64 columns]
     // fp32 (v = value transform), from where each lane reads 4 consecutive columns of a row.  The 16-column
@@ -1077,6 +1077,12 @@ ms_status gemm_swiglu(int M, int F, int K, const void *A, long lda, const void *
     else launch_fast_epi<128, 128, 2, 2, EPI_SWIGLU>(p, grid, s);
     MS_LAUNCH_CHECK();
     return MS_OK;
+}
+
+extern "C" ms_status ms_k_gemm_swiglu(int32_t M, int32_t F, int32_t K, const void *A, int64_t lda, const void *W, int64_t ldw,
+                                      void *act, int64_t ldact, void *gate_up, int64_t ldgu, void *stream) {
+    if (!A || !W || !act) return ms_fail(MS_ERR_INVALID_ARG, "gemm_swiglu: null pointer");
+    return gemm_swiglu(M, F, K, A, lda, W, ldw, act, ldact, gate_up, ldgu, (hipStream_t)stream);
 }
 
 // ------------------------------------------------------------------ matrix-core rate probe

@@ -9,8 +9,14 @@
 // On the bf16 fast path the student logits are never stored: the epilogue of their GEMM reads the
 // teacher logits of the same tile and emits per-strip partial statistics (pass 1, merged per token
 // by a small kernel) or dz itself (pass 2).
+#include <mutex>
+
 #include "common.h"
 #include "launch.h"
+
+// Scratch of ms_kd_loss_forward_backward_static: one copy per GPU, held until the process ends.  In host code this
+// name is only a handle for hipGetSymbolAddress; the device address it yields is what kernels and fills receive.
+static __device__ __align__(256) unsigned char scratch[MS_KD_STATIC_SCRATCH_BYTES];
 
 namespace {
 
@@ -297,4 +303,40 @@ extern "C" ms_status ms_kd_loss_forward_backward(const ms_kd_config *kd, int32_t
                                                  size_t workspace_bytes, void *stream) {
     return kd_forward_backward(kd, n_tokens, h_teacher, h_student, loss_dev, kl_per_token_dev, d_h_student, d_w_student,
                                workspace_dev, workspace_bytes, (hipStream_t)stream);
+}
+
+// ------------------------------------------------------------------ allocation-free variant
+namespace {
+constexpr int kMaxDevices = 64;
+void *g_scratch_dev[kMaxDevices];       // device address of `scratch` on each GPU, resolved on first use
+std::mutex g_scratch_mutex;
+
+ms_status static_scratch(void **out) {
+    int dev = -1;
+    MS_CHECK_HIP(hipGetDevice(&dev));
+    if (dev < 0 || dev >= kMaxDevices) return ms_fail(MS_ERR_UNSUPPORTED, "kd_static: device index %d out of range", dev);
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_dev[dev]) {
+        void *p = nullptr;
+        MS_CHECK_HIP(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+        if (!p) return ms_fail(MS_ERR_HIP, "kd_static: no device address for the scratch array");
+        g_scratch_dev[dev] = p;
+    }
+    *out = g_scratch_dev[dev];
+    return MS_OK;
+}
+}  // namespace
+
+extern "C" ms_status ms_kd_loss_forward_backward_static(const ms_kd_config *kd, int32_t n_tokens, const void *h_teacher,
+                                                        const void *h_student, float *loss_dev, float *kl_per_token_dev,
+                                                        void *d_h_student, void *d_w_student, void *stream) {
+    MS_TRY(validate_kd(kd, n_tokens));
+    const size_t need = kd_plan(kd, n_tokens, nullptr).bytes;
+    if (need > (size_t)MS_KD_STATIC_SCRATCH_BYTES)
+        return ms_fail(MS_ERR_WORKSPACE, "kd_static: %d tokens x chunk %d need %zu bytes of scratch, the built-in buffer holds %zu",
+                       n_tokens, kd->chunk, need, (size_t)MS_KD_STATIC_SCRATCH_BYTES);
+    void *ws = nullptr;
+    MS_TRY(static_scratch(&ws));
+    return kd_forward_backward(kd, n_tokens, h_teacher, h_student, loss_dev, kl_per_token_dev, d_h_student, d_w_student, ws,
+                               (size_t)MS_KD_STATIC_SCRATCH_BYTES, (hipStream_t)stream);
 }

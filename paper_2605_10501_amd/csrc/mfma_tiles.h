@@ -25,6 +25,16 @@ __device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void *p, long 
     return __builtin_amdgcn_make_buffer_rsrc(const_cast<void *>(p), 0, (int)(unsigned)bytes, 0x00020000);
 }
 
+// Barrier that hands a tile filled by direct-to-LDS loads to the other waves of the workgroup: a wave's own
+// loads must have landed (vmcnt(0): the loads complete in order, and at every such barrier all outstanding ones
+// belong to the tile being published) before it tells the others so.  The wait is written out rather than left
+// to the compiler's lowering of the barrier's fence.  s_waitcnt operand (gfx9 encoding): vmcnt = bits 3:0 and
+// 15:14, expcnt = bits 6:4, lgkmcnt = bits 11:8; 0x0F70 waits for vmcnt(0) only.
+__device__ __forceinline__ void dma_publish_barrier() {
+    __builtin_amdgcn_s_waitcnt(0x0F70);
+    __syncthreads();
+}
+
 // ---- transposing LDS read (ds_read_b64_tr_b16) --------------------------------------------------
 // Within each group of 16 lanes, lane r supplies the address of an 8-byte row (4 bf16); lane i
 // receives element i%4 of rows i/4, 4 + i/4, 8 + i/4, 12 + i/4.  With a tile stored [k][m]

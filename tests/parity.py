@@ -14,7 +14,7 @@ rounding noise of about sqrt(stages) * 1.7e-3 relative (tests/test_oracle_sectio
 this between two oracle runs that differ by 1e-6 relative perturbations).  With ~4e-3 rms noise
 the 2e-2 bound is a 5-sigma event, so on tensors of 10^5 .. 10^7 elements a handful of elements
 may exceed it although nothing is wrong.  The chain criterion therefore requires
-  rms(err) <= tol / 3,  99.9 % of the elements <= tol,  every element <= 3 tol.
+  rms(err) <= tol / 4,  99.9 % of the elements <= tol,  every element <= 3 tol.
 
 assert_parity_vs_noise: for deep, wide stacks (the full-size workloads: 4-8 layers at d = 1024..4096)
 that rounding noise itself exceeds the chain numbers: two runs of the ORACLE under the bf16 contract,
@@ -49,14 +49,52 @@ def assert_parity(gpu, ref, tol, name=""):
     return mx
 
 
+def assert_parity_rows(gpu, ref, tol, name=""):
+    """assert_parity with the error floor taken per row: err = |gpu - ref| / max(|ref|, rms(ref[row, :])).
+
+    For attention-shaped tensors of packed variable-length batches (o, dq, dk, dv: one row per token) the scale of a
+    row depends on how many keys (or queries) it sees -- |o| ~ 1/sqrt(keys) for unit-variance values -- so under a
+    tensor-wide floor the rows of a 4096-token sequence set the floor for the first rows of every sequence, whose
+    elements are 10-60 x larger, and an element of such a row that happens to be small compared with ITS OWN row is
+    judged against a floor that is smaller still.  Rounding the probabilities to bf16 where they enter the P V product
+    (the one step the oracle's forward pass does not round) then exceeds 2e-2 on ~20 of 524288 elements at L = 4096
+    (CPU emulation with the oracle's own routines: max 2.6e-2, all in the first ~50 rows), and on none under the
+    per-row floor (max 1.1e-2).  Rows that see many keys get a LOWER floor than the tensor-wide one.  A row may vanish
+    identically (dq of a causal sequence's first token: P = 1, dS = dP - delta = 0), where an fp32 path leaves
+    cancellation noise of ~1e-7; the floor is therefore never below 1e-3 of the tensor-wide rms."""
+    g = gpu.detach().to(torch.float64).cpu().numpy() if isinstance(gpu, torch.Tensor) else np.asarray(gpu, np.float64)
+    r = np.asarray(ref, dtype=np.float64).reshape(g.shape)
+    floor = np.maximum(np.sqrt(np.mean(r * r, axis=-1, keepdims=True)), 1e-3 * np.sqrt(np.mean(r * r)))
+    e = np.abs(g - r) / np.maximum(np.abs(r), np.maximum(floor, 1e-300))
+    assert np.all(np.isfinite(e)), f"{name}: non-finite values"
+    mx = float(e.max()) if e.size else 0.0
+    assert mx <= tol, f"{name}: max err {mx:.3e} > {tol:.1e} (p99.9 {np.quantile(e, 0.999):.3e}, at {np.unravel_index(e.argmax(), e.shape)})"
+    return mx
+
+
+def assert_kl_tok(gpu, ref, tol, vocab, name="kl_tok"):
+    """Per-token KL terms.  A path that never holds a token's full logit row gets KL_t from running statistics as
+    A / s_t - lse_t + lse_s: a small number (1e-3 .. 1e-1) left over from log-sum-exps of magnitude ~ln(vocab), each
+    of which an fp32 path knows to about an ulp.  The comparison therefore allows, besides the relative tolerance of
+    the loss, an absolute term of 16 ulp_fp32(ln vocab) = 16 * 2^-24 * ln(vocab)  (~7e-6 at vocab 1024, 1.1e-5 at
+    151936); the scalar loss, where these errors average out, is held to the plain relative tolerance."""
+    g = gpu.detach().to(torch.float64).cpu().numpy() if isinstance(gpu, torch.Tensor) else np.asarray(gpu, np.float64)
+    r = np.asarray(ref, dtype=np.float64).reshape(g.shape)
+    rms = float(np.sqrt(np.mean(r * r))) if r.size else 0.0
+    bound = tol * np.maximum(np.abs(r), rms) + 16.0 * 2.0 ** -24 * np.log(float(vocab))
+    bad = np.abs(g - r) > bound
+    assert np.all(np.isfinite(g)) and not bad.any(), \
+        f"{name}: {int(bad.sum())} tokens outside tol {tol:.1e} + abs {16.0 * 2.0 ** -24 * np.log(float(vocab)):.1e}; worst |diff| {np.abs(g - r).max():.3e}, rms(ref) {rms:.3e}"
+
+
 def assert_parity_chain(gpu, ref, tol, name=""):
     e = rel_err(gpu, ref)
     assert np.all(np.isfinite(e)), f"{name}: non-finite values"
     if e.size == 0:
         return 0.0
     mx, q, rms = float(e.max()), float(np.quantile(e, 0.999)), float(np.sqrt(np.mean(e * e)))
-    assert rms <= tol / 3 and q <= tol and mx <= 3 * tol, \
-        f"{name}: rms {rms:.3e} (<= {tol / 3:.1e}), p99.9 {q:.3e} (<= {tol:.1e}), max {mx:.3e} (<= {3 * tol:.1e})"
+    assert rms <= tol / 4 and q <= tol and mx <= 3 * tol, \
+        f"{name}: rms {rms:.3e} (<= {tol / 4:.1e}), p99.9 {q:.3e} (<= {tol:.1e}), max {mx:.3e} (<= {3 * tol:.1e})"
     return mx
 
 

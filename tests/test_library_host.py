@@ -85,3 +85,12 @@ def test_workspace_sizes():
     assert B.section_workspace_bytes(wl.scaled(c2.student, head_dim=100), 16, 16, True) == 0
     kd = B.kd_workspace_bytes(wl.workload("c3").kd, 8192)
     assert kd >= 2 * 8192 * 8192 * 4 and kd < 2 << 30
+
+
+def test_static_scratch_kd_call_rejects_oversize_before_touching_the_device():
+    kd = wl.KDConfig(151936, 4096, 2048, 2.0, 8192)
+    c = B.KDConfigC(kd.vocab, kd.h_teacher, kd.h_student, kd.chunk, B.MS_BF16, kd.temperature, 1.0, 256, 256, 0)
+    fake = C.c_void_p(256)
+    assert B.kd_workspace_bytes(kd, 8192) > B.KD_STATIC_SCRATCH_BYTES
+    assert B.lib().ms_kd_loss_forward_backward_static(C.byref(c), 8192, fake, fake, fake, fake, fake, fake, None) == -3
+    assert b"built-in buffer" in B.lib().ms_last_error()

@@ -126,3 +126,38 @@ def test_backward_finite_difference(rng, causal):
     for idx in [(0, 0, 0), (3, 1, 2), (5, 0, 1), (8, 1, 3)]:
         assert dk[idx] == pytest.approx(fd_grad(f, k, idx), rel=1e-6, abs=1e-9)
         assert dv[idx] == pytest.approx(fd_grad(f, v, idx), rel=1e-6, abs=1e-9)
+
+
+@pytest.mark.parametrize("causal", [True, False])
+def test_operand_rounding_hook_sees_p_and_ds_only(rng, causal):
+    """rnd_p is applied to P (for dV) and to dS = P * (dP - delta) (for dQ, dK), and to nothing else."""
+    from oracle import round_bf16
+    L, hd = 5, 4
+    q, k, v, do = (rng.standard_normal((L, 1, hd)) for _ in range(4))
+    # P, dP, delta by loops
+    P = np.zeros((L, L))
+    for i in range(L):
+        js = range(i + 1) if causal else range(L)
+        e = {j: math.exp(sum(q[i, 0, d] * k[j, 0, d] for d in range(hd)) / math.sqrt(hd)) for j in js}
+        z = sum(e.values())
+        for j in js:
+            P[i, j] = e[j] / z
+    dP = np.array([[sum(do[i, 0, d] * v[j, 0, d] for d in range(hd)) for j in range(L)] for i in range(L)])
+    delta = np.array([sum(P[i, j] * dP[i, j] for j in range(L)) for i in range(L)])
+    dS = P * (dP - delta[:, None])
+    seen = []
+    def hook(x):
+        seen.append(np.array(x))
+        return 2.0 * x                      # not a rounding: makes every use of the hook's output visible
+    dq, dk, dv = attention_bwd(do, q, k, v, [0, L], causal, rnd_p=hook)
+    assert len(seen) == 2 and np.allclose(seen[0], P, atol=1e-14) and np.allclose(seen[1], dS, atol=1e-14)
+    dq0, dk0, dv0 = attention_bwd(do, q, k, v, [0, L], causal)
+    # each gradient is linear in exactly one hooked matrix (dP and delta do not pass through the hook: no factor 4)
+    assert np.allclose(dq, 2 * dq0) and np.allclose(dk, 2 * dk0) and np.allclose(dv, 2 * dv0)
+    # with the bf16 rounding the gradients stay within the rounding bound |x - rnd(x)| <= 2^-8 |x| of each operand element
+    dqr, dkr, dvr = attention_bwd(do, q, k, v, [0, L], causal, rnd_p=round_bf16)
+    u = 2.0 ** -8                            # half an ulp of an 8-bit significand
+    assert np.all(np.abs(dvr - dv0)[:, 0] <= u * (P.T @ np.abs(do[:, 0])) + 1e-15)
+    assert np.all(np.abs(dqr - dq0)[:, 0] <= u * (np.abs(dS) @ np.abs(k[:, 0])) / math.sqrt(hd) + 1e-15)
+    assert np.all(np.abs(dkr - dk0)[:, 0] <= u * (np.abs(dS).T @ np.abs(q[:, 0])) / math.sqrt(hd) + 1e-15)
+    assert not np.array_equal(dqr, dq0)
