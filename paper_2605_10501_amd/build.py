@@ -9,7 +9,8 @@ ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 OUT = os.path.join(HERE, "libmaestro_section.so")
 BUILD = os.path.join(ROOT, "_build")
-SOURCES = ["api.cpp", "scheduler.cpp", "elementwise.hip", "gemm.hip", "attention.hip", "attention_mfma.hip", "kd.hip", "section.hip", "merger.hip"]
+SOURCES = ["api.cpp", "profile.cpp", "scheduler.cpp", "kd_host.cpp", "elementwise.hip", "gemm.hip", "attention.hip", "attention_mfma.hip", "kd.hip",
+           "section.hip", "merger.hip", "probes.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-fPIC", "-std=c++17", "-x", "hip",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
          "-I", os.path.join(ROOT, "include"), "-I", CSRC, "-Wno-unused-value"]

@@ -567,7 +567,7 @@ ms_status launch_fwd(int causal, int nq, int nkv, int n, int n_seqs, int max_seq
                      void *o, float *lse, hipStream_t s) {
     const int ntile_max = ms_cdiv(max_seqlen, 128);
     const long blocks = (long)ntile_max * nq * n_seqs;
-    if (blocks > 0x7fffffffL || (long)n * (nq + 2 * nkv) * HD * 2 >= (1L << 32) - (1L << 20))
+    if (blocks > 0x7fffffffL || !ms_attn_offsets_fit(n, nq, nkv, HD))
         return ms_fail(MS_ERR_UNSUPPORTED, "attention: batch too large for 32-bit tile offsets");
     const float sc = 1.4426950408889634f / sqrtf((float)HD);
     if (causal) attn_fwd_mfma_kernel<HD, true><<<(unsigned)blocks, 256, 0, s>>>((const bf16_t *)qkv, (bf16_t *)o, lse, cu, n, nq, nkv, n_seqs, ntile_max, sc);
@@ -585,7 +585,7 @@ ms_status launch_bwd(int causal, int nq, int nkv, int n, int n_seqs, int max_seq
     const float scale = 1.f / sqrtf((float)HD);
     const int ntile_max = ms_cdiv(max_seqlen, 128);
     const long blocks = (long)ntile_max * nq * n_seqs;
-    if (blocks > 0x7fffffffL || (long)n * (nq + 2 * nkv) * HD * 2 >= (1L << 32) - (1L << 20))
+    if (blocks > 0x7fffffffL || !ms_attn_offsets_fit(n, nq, nkv, HD))
         return ms_fail(MS_ERR_UNSUPPORTED, "attention: batch too large for 32-bit tile offsets");
     // grouped-query attention: split the group's query heads over workgroups (see the kernel)
     const bool split = nq / nkv > 1;

@@ -32,6 +32,14 @@ static inline size_t ms_align_up(size_t x, size_t a = 256) { return (x + a - 1) 
 static inline int ms_cdiv(long a, long b) { return (int)((a + b - 1) / b); }
 static inline size_t ms_dtype_size(int dtype) { return dtype == MS_BF16 ? 2 : 4; }
 
+// Shape limits of the kernels, in one place so that a section call can check them before its first launch.
+constexpr int kNormMaxCache = 8;   // 16-byte vectors of a row that a lane of the norm kernels keeps in registers
+static inline int ms_norm_backward_max_d(int dtype) { return 64 * kNormMaxCache * (dtype == MS_BF16 ? 8 : 4); }
+// the matrix-core attention kernels address qkv through 32-bit byte offsets
+static inline bool ms_attn_offsets_fit(long n, int nq, int nkv, int hd) {
+    return n * (nq + 2 * nkv) * hd * 2 < (1L << 32) - (1L << 20);
+}
+
 // Linear carve-out of the caller's workspace; every piece 256-byte aligned.
 struct Arena {
     char *base;

@@ -6,7 +6,7 @@
 
 namespace {
 
-constexpr int kMaxCache = 8;       // 16-byte vectors a lane keeps in registers per row
+constexpr int kMaxCache = kNormMaxCache;   // 16-byte vectors a lane keeps in registers per row
 constexpr int kPartialRows = 1024; // rows of the partial-sum scratch of column reductions
 
 // ------------------------------------------------------------------ norm forward
@@ -496,9 +496,9 @@ extern "C" ms_status ms_k_norm_backward(int32_t kind, int32_t dtype, int32_t x_f
     if (!dy || !x || !g || !rstd || !dx || !dg || !scratch || (kind == 1 && (!mean || !db)) || n < 0 || d <= 0)
         return ms_fail(MS_ERR_INVALID_ARG, "norm_backward: null pointer or bad size");
     const int V = dtype == MS_BF16 ? 8 : 4;
-    if (d % V || d > 64 * kMaxCache * V)
+    if (d % V || d > ms_norm_backward_max_d(dtype))
         return ms_fail(MS_ERR_UNSUPPORTED, "norm_backward: d=%d must be a multiple of %d and at most %d", d, V,
-                       64 * kMaxCache * V);
+                       ms_norm_backward_max_d(dtype));
     hipStream_t s = (hipStream_t)stream;
     float *pg = (float *)scratch;
     float *pb = (float *)((char *)scratch + ms_align_up((size_t)kPartialRows * d * sizeof(float)));

@@ -1,20 +1,24 @@
 // GEMM kernels of the section path.
 //
-// bf16: C = alpha * A(m,k) B(n,k) on the CDNA4 matrix cores (v_mfma_f32_32x32x16_bf16).
-//   * workgroup = 256 threads = 4 waves in a 2x2 grid, workgroup tile BM x BN x 64;
-//   * both operands are staged global -> registers -> LDS with a one-tile register prefetch and
-//     two LDS buffers, so one barrier per K tile is enough;
-//   * LDS rows are 64 bf16 (128 B) = eight 16-byte chunks; chunk c of row r is stored at chunk
-//     c ^ (r & 7) ^ ((r >> 3) & 3), which spreads the fragment reads (32 consecutive rows, one
-//     chunk) over the banks;
-//   * an operand stored K-major ("transposed": weight gradients, input gradients) is
-//     transposed in registers while it is staged: a thread loads an 8(k) x 8(m) block as eight
-//     16-byte rows and writes eight 16-byte K-contiguous rows, so the MFMA loop is the same for
-//     all four layouts;
-//   * workgroup ids are remapped so that the ids one XCD receives (id mod 8) are neighbours in
-//     tile space and share operand panels in that XCD's L2.
+// bf16: C = alpha * A(m,k) B(n,k) on the CDNA4 matrix cores, all four operand layouts.
+//   * gemm_bf16_fast_kernel: workgroup tile 256 x 256 x 64 (8 waves, wave tile 128 x 64, one workgroup per CU) or
+//     128 x 128 x 64 (4 waves, two per CU); v_mfma_f32_16x16x32_bf16 by default (v_mfma_f32_32x32x16_bf16 selectable);
+//   * every operand tile goes global -> LDS directly (buffer_load ... lds), two LDS buffers per operand, one barrier
+//     per K tile; a K-contiguous operand lands as [rows][64] with the 16-byte chunk index XOR-swizzled (applied on the
+//     global side of the load), a K-major operand (weight gradients, input gradients) lands as a row tile and is read
+//     through the transposing LDS load (ds_read_b64_tr_b16), so no layout needs a transposed copy;
+//   * fragments are double-buffered in registers, LDS reads of the next k-step interleaved with the MFMAs;
+//   * epilogues (bias, bf16 / fp32 residual, fp32 or bf16 output, accumulate, fused SwiGLU, fused KD statistics / dz)
+//     pass the accumulators through the idle LDS buffers so that each lane stores 4 consecutive columns, with
+//     non-temporal global accesses; split-K uses fp32 atomics;
+//   * workgroup ids are remapped so that each XCD works on a contiguous range of tiles, ordered in groups of M-tiles
+//     x all N-tiles, and shares operand panels in its L2;
+//   * gemm_bf16_kernel is the register-staged, bounds-checked fallback (K not a multiple of 64 with a K-contiguous
+//     operand, matrices of 4 GB and more).
 // fp32: a plain LDS-tiled FMA kernel (correctness path of the fp32 workload).
 #include <stdlib.h>
+
+#include <atomic>
 
 #include "common.h"
 #include "launch.h"
@@ -840,18 +844,22 @@ MS_INST(128, 2, false, false); MS_INST(128, 2, false, true); MS_INST(128, 2, tru
 MS_INST_EPI(EPI_KD_DZ); MS_INST_EPI(EPI_KD_STATS); MS_INST_EPI(EPI_SWIGLU);
 #undef MS_INST_EPI
 
-// Kernel selection switches (measurements and tests): the environment gives the process-wide setting
+// Kernel selection switches, for measurements and tests only: the environment gives the process-wide setting
 // (MS_GEMM_TILE = 128 / 256 forces the fast kernels' tile, -1 disables them; MS_GEMM_MFMA16 = 0 selects
-// v_mfma_f32_32x32x16_bf16), ms_k_gemm_config overrides it at run time.
+// v_mfma_f32_32x32x16_bf16), ms_k_gemm_config overrides it at run time.  The overrides are atomics, so changing them
+// from one thread while another launches is defined, but which setting a concurrent launch sees is not: production
+// callers leave them alone (automatic choice by shape).
 constexpr int kUnset = -1000;
-int g_tile_override = kUnset, g_mfma16_override = kUnset;
+std::atomic<int> g_tile_override{kUnset}, g_mfma16_override{kUnset};
 int forced_tile() {
     static const int env = [] { const char *e = getenv("MS_GEMM_TILE"); return e ? atoi(e) : 0; }();
-    return g_tile_override != kUnset ? g_tile_override : env;
+    const int o = g_tile_override.load(std::memory_order_relaxed);
+    return o != kUnset ? o : env;
 }
 bool use_mfma16() {
     static const bool env = [] { const char *e = getenv("MS_GEMM_MFMA16"); return !e || atoi(e) != 0; }();
-    return g_mfma16_override != kUnset ? g_mfma16_override != 0 : env;
+    const int o = g_mfma16_override.load(std::memory_order_relaxed);
+    return o != kUnset ? o != 0 : env;
 }
 
 template <int BM, int BN, int WM, int WN, int EPI>
@@ -1083,79 +1091,4 @@ extern "C" ms_status ms_k_gemm_swiglu(int32_t M, int32_t F, int32_t K, const voi
                                       void *act, int64_t ldact, void *gate_up, int64_t ldgu, void *stream) {
     if (!A || !W || !act) return ms_fail(MS_ERR_INVALID_ARG, "gemm_swiglu: null pointer");
     return gemm_swiglu(M, F, K, A, lda, W, ldw, act, ldact, gate_up, ldgu, (hipStream_t)stream);
-}
-
-// ------------------------------------------------------------------ matrix-core rate probe
-namespace {
-template <bool M16>
-__global__ __launch_bounds__(512) void mfma_probe_kernel(int iters, int random_operands, float *sink) {
-    // the same flops per iteration for both shapes: 8 x 32x32x16 or 16 x 16x16x32, all independent
-    constexpr int NACC = M16 ? 16 : 8, ACC_N = M16 ? 4 : 16;
-    std::conditional_t<M16, f32x4, f32x16> acc[NACC];
-#pragma unroll
-    for (int i = 0; i < NACC; ++i)
-#pragma unroll
-        for (int r = 0; r < ACC_N; ++r) acc[i][r] = 0.f;
-    bf16x8 a, b;
-#pragma unroll
-    for (int e = 0; e < 8; ++e) { a[e] = (bf16_t)(float)(threadIdx.x & 3); b[e] = (bf16_t)(1.f / 64.f); }
-    if (random_operands) {
-        // random sign and mantissa, magnitudes 2^-4 .. 2^4: the bit activity of real activations and weights,
-        // which is what the chip's power management reacts to
-#pragma unroll
-        for (int e = 0; e < 8; ++e) {
-            unsigned h = (threadIdx.x * 8u + e) * 2654435761u + blockIdx.x * 40503u;
-            h ^= h >> 15; h *= 2246822519u; h ^= h >> 13;
-            unsigned g = h * 2654435761u + 12345u;
-            g ^= g >> 16; g *= 2246822519u; g ^= g >> 13;
-            a[e] = __builtin_bit_cast(bf16_t, (unsigned short)(((h & 1) << 15) | ((123 + ((h >> 1) & 7)) << 7) | ((h >> 4) & 127)));
-            b[e] = __builtin_bit_cast(bf16_t, (unsigned short)(((g & 1) << 15) | ((123 + ((g >> 1) & 7)) << 7) | ((g >> 4) & 127)));
-        }
-    }
-    for (int it = 0; it < iters; ++it) {
-#pragma unroll
-        for (int i = 0; i < NACC; ++i) {
-            if constexpr (M16) acc[i] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b, acc[i], 0, 0, 0);
-            else acc[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, acc[i], 0, 0, 0);
-        }
-    }
-    float t = 0.f;
-#pragma unroll
-    for (int i = 0; i < NACC; ++i)
-#pragma unroll
-        for (int r = 0; r < ACC_N; ++r) t += acc[i][r];
-    sink[(long)blockIdx.x * 512 + threadIdx.x] = t;
-}
-
-// One wave that watches the clocks for a given time while other kernels run: the shader-clock counter
-// (s_memtime) against the constant 100 MHz counter (s_memrealtime).  Ends after `ticks_100mhz` of the constant
-// counter or after max_polls polls, whichever comes first.
-__global__ __launch_bounds__(64) void clock_monitor_kernel(long ticks_100mhz, long max_polls, long long *out) {
-    const long long c0 = clock64(), w0 = wall_clock64();
-    long long w1 = w0;
-    for (long i = 0; i < max_polls && w1 - w0 < ticks_100mhz; ++i) {
-        __builtin_amdgcn_s_sleep(64);
-        w1 = wall_clock64();
-    }
-    const long long c1 = clock64();
-    w1 = wall_clock64();
-    if (threadIdx.x == 0) { out[0] = c1 - c0; out[1] = w1 - w0; }
-}
-}  // namespace
-
-extern "C" ms_status ms_k_clock_monitor(int32_t microseconds, int64_t *out_dev, void *stream) {
-    if (microseconds <= 0 || microseconds > 1000000 || !out_dev) return ms_fail(MS_ERR_INVALID_ARG, "clock_monitor: bad argument");
-    // a poll takes at least the 64 x 64 clocks of its sleep (> 1.5 us at any clock this chip runs at)
-    clock_monitor_kernel<<<1, 64, 0, (hipStream_t)stream>>>(100L * microseconds, 2L * microseconds + 1000, (long long *)out_dev);
-    MS_LAUNCH_CHECK();
-    return MS_OK;
-}
-
-extern "C" ms_status ms_k_mfma_probe(int32_t workgroups, int32_t iters, int32_t random_operands, int32_t mfma16, float *sink_dev,
-                                     void *stream) {
-    if (workgroups <= 0 || iters <= 0 || !sink_dev) return ms_fail(MS_ERR_INVALID_ARG, "mfma_probe: bad argument");
-    if (mfma16) mfma_probe_kernel<true><<<workgroups, 512, 0, (hipStream_t)stream>>>(iters, random_operands, sink_dev);
-    else mfma_probe_kernel<false><<<workgroups, 512, 0, (hipStream_t)stream>>>(iters, random_operands, sink_dev);
-    MS_LAUNCH_CHECK();
-    return MS_OK;
 }

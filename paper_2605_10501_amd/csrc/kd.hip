@@ -13,6 +13,7 @@
 
 #include "common.h"
 #include "launch.h"
+#include "kd_host.h"
 
 // Scratch of ms_kd_loss_forward_backward_static: one copy per GPU, held until the process ends.  In host code this
 // name is only a handle for hipGetSymbolAddress; the device address it yields is what kernels and fills receive.
@@ -20,7 +21,7 @@ static __device__ __align__(256) unsigned char scratch[MS_KD_STATIC_SCRATCH_BYTE
 
 namespace {
 
-constexpr int kStat = 8;  // floats per token: m_t, s_t, m_s, s_s, A, KL, lse_t, lse_s
+constexpr int kStat = kKdStat;  // floats per token: m_t, s_t, m_s, s_s, A, KL, lse_t, lse_s
 
 __device__ __forceinline__ float block_max(float v, float *sm) {
     v = wave_max(v);
@@ -170,53 +171,7 @@ __global__ __launch_bounds__(256) void kd_combine_kernel(const float *__restrict
     }
 }
 
-struct KdPlan {
-    float *zt, *zs, *stats, *dhs;
-    void *dz;
-    size_t bytes;
-    int tb;            // tokens per block
-    bool keep;         // teacher logits of a block are kept across the two passes (one [tb, chunk] slab per chunk)
-};
-
-// token_block > 0: the tokens are processed in blocks of that many, and the teacher logits of the current block
-// stay in the workspace between the statistics pass and the gradient pass (no teacher recompute); the cache
-// is [n_chunks][token_block][chunk] fp32, independent of the number of tokens.
-KdPlan kd_plan(const ms_kd_config *kd, int n, void *ws) {
-    Arena a(ws);
-    KdPlan p;
-    p.keep = kd->token_block > 0;
-    p.tb = p.keep && kd->token_block < n ? kd->token_block : n;
-    const size_t nc = (size_t)p.tb * kd->chunk;
-    const size_t nchunks = p.keep ? (size_t)ms_cdiv(kd->vocab, kd->chunk) : 1;
-    p.zt = a.take<float>(nchunks * nc * 4);
-    p.zs = a.take<float>(nc * 4);
-    p.stats = a.take<float>((size_t)n * kStat * 4);
-    p.dz = a.take<void>(nc * ms_dtype_size(kd->dtype));
-    p.dhs = a.take<float>((size_t)n * kd->h_student * 4);
-    p.bytes = a.off;
-    return p;
-}
-
 }  // namespace
-
-ms_status validate_kd(const ms_kd_config *kd, int n_tokens) {
-    if (!kd) return ms_fail(MS_ERR_INVALID_ARG, "kd: null config");
-    if (n_tokens < 0) return ms_fail(MS_ERR_INVALID_ARG, "kd: negative token count");
-    if (kd->dtype != MS_BF16 && kd->dtype != MS_F32) return ms_fail(MS_ERR_INVALID_ARG, "kd: bad dtype");
-    if (kd->vocab <= 0 || kd->h_teacher <= 0 || kd->h_student <= 0 || kd->chunk <= 0)
-        return ms_fail(MS_ERR_SHAPE, "kd: vocab, hidden sizes and chunk must be positive");
-    if (!(kd->temperature > 0.f)) return ms_fail(MS_ERR_INVALID_ARG, "kd: temperature must be positive");
-    if (kd->token_block < 0 || kd->token_block % 8) return ms_fail(MS_ERR_INVALID_ARG, "kd: token_block must be 0 or a positive multiple of 8");
-    if (kd->vocab % 8 || kd->chunk % 8 || kd->h_teacher % 8 || kd->h_student % 8)
-        return ms_fail(MS_ERR_UNSUPPORTED, "kd: vocab, chunk and hidden sizes must be multiples of 8");
-    if (!kd->w_teacher_dev || !kd->w_student_dev) return ms_fail(MS_ERR_INVALID_ARG, "kd: null lm_head pointer");
-    return MS_OK;
-}
-
-extern "C" size_t ms_kd_workspace_bytes(const ms_kd_config *kd, int32_t max_tokens) {
-    if (!kd || max_tokens < 0 || kd->chunk <= 0 || kd->h_student <= 0) return 0;
-    return kd_plan(kd, max_tokens, nullptr).bytes;
-}
 
 ms_status kd_forward_backward(const ms_kd_config *kd, int n, const void *h_t, const void *h_s, float *loss_dev,
                               float *kl_tok_dev, void *d_h_s, void *d_w_s, void *workspace, size_t workspace_bytes,

@@ -103,6 +103,17 @@ ms_status validate_config(const ms_section_config *c) {
     return MS_OK;
 }
 
+// Limits of the kernels this call will launch, so that nothing fails after the first launch.
+ms_status validate_limits(const ms_section_config *c, int n_tokens, bool backward) {
+    if (backward && c->d_model > ms_norm_backward_max_d(c->dtype))
+        return ms_fail(MS_ERR_UNSUPPORTED, "section: d_model=%d above %d, the widest row the norm backward kernel holds",
+                       c->d_model, ms_norm_backward_max_d(c->dtype));
+    if (c->dtype == MS_BF16 && !ms_attn_offsets_fit(n_tokens, c->n_q_heads, c->n_kv_heads, c->head_dim))
+        return ms_fail(MS_ERR_UNSUPPORTED, "section: %d tokens x %d qkv columns exceed the 4 GiB the attention kernels address",
+                       n_tokens, (c->n_q_heads + 2 * c->n_kv_heads) * c->head_dim);
+    return MS_OK;
+}
+
 ms_status validate_batch(const ms_batch *b, int *max_seqlen) {
     if (!b) return ms_fail(MS_ERR_INVALID_ARG, "section: null batch");
     if (b->n_tokens < 0 || b->n_seqs < 0) return ms_fail(MS_ERR_INVALID_ARG, "section: negative batch size");
@@ -229,6 +240,7 @@ extern "C" ms_status ms_section_forward(const ms_section_config *cfg, const ms_s
     int max_seqlen = 0;
     MS_TRY(validate_batch(batch, &max_seqlen));
     if (batch->n_tokens == 0) return MS_OK;
+    MS_TRY(validate_limits(cfg, batch->n_tokens, false));
     MS_TRY(validate_ptrs(cfg, weights, "weights"));
     if (!x_in || !h_out || !workspace_dev) return ms_fail(MS_ERR_INVALID_ARG, "section_forward: null pointer");
     Plan p = make_plan(cfg, batch->n_tokens, max_seqlen, false, workspace_dev);
@@ -273,6 +285,7 @@ extern "C" ms_status ms_section_forward_backward(const ms_section_config *cfg, c
             return ms_fail(MS_ERR_SHAPE, "section_forward_backward: kd->h_student / dtype do not match the section");
         if (!loss_dev) return ms_fail(MS_ERR_INVALID_ARG, "section_forward_backward: loss_dev is null");
     }
+    MS_TRY(validate_limits(cfg, batch->n_tokens, true));
     MS_TRY(validate_ptrs(cfg, weights, "weights"));
     MS_TRY(validate_ptrs(cfg, grads, "grads"));
     if (!x_in || !h_out || !workspace_dev || (kd && !h_teacher))

@@ -111,11 +111,19 @@ def perturbed_rounding(seed, rel=1e-6):
 
 
 def assert_parity_vs_noise(gpu, ref, ref_perturbed, name="", factor=1.5, cap_rms=2e-2, cap_max=0.15):
+    """GPU error against the oracle <= factor x the error of the perturbed oracle run against the same oracle, for
+    the rms and a high quantile, and <= 2 x factor for the maximum.  The quantile is p99.9 where that leaves at least
+    ten elements above it, else 1 - 10 / size (on a 1280-element gain gradient p99.9 IS the largest element, whose
+    ratio between two noise realisations is not bounded by 1.5).  Absolute caps keep the check from becoming vacuous:
+    rms <= cap_rms always; the maximum <= cap_max unless the noise floor's own maximum is that large (weight gradients
+    of a few hundred tokens have such elements: sums of few terms), in which case it may exceed the floor's by 25 %."""
     e, f = rel_err(gpu, ref), rel_err(ref_perturbed, ref)
     assert np.all(np.isfinite(e)), f"{name}: non-finite values"
-    stats = lambda v: (float(np.sqrt(np.mean(v * v))), float(np.quantile(v, 0.999)), float(v.max()))
+    ql = min(0.999, max(0.5, 1.0 - 10.0 / max(e.size, 1)))
+    stats = lambda v: (float(np.sqrt(np.mean(v * v))), float(np.quantile(v, ql)), float(v.max()))
     (er, eq, em), (fr, fq, fm) = stats(e), stats(f)
-    msg = f"{name}: gpu-vs-oracle rms {er:.3e} p99.9 {eq:.3e} max {em:.3e}; noise floor rms {fr:.3e} p99.9 {fq:.3e} max {fm:.3e}"
+    msg = (f"{name}: gpu-vs-oracle rms {er:.3e} p{100 * ql:.1f} {eq:.3e} max {em:.3e}; noise floor rms {fr:.3e} "
+           f"p{100 * ql:.1f} {fq:.3e} max {fm:.3e}")
     assert er <= factor * fr and eq <= factor * fq and em <= 2 * factor * fm, msg
-    assert er <= cap_rms and em <= cap_max, msg
+    assert er <= cap_rms and em <= max(cap_max, 1.25 * fm), msg
     return msg
