@@ -40,14 +40,15 @@ static inline bool ms_attn_offsets_fit(long n, int nq, int nkv, int hd) {
     return n * (nq + 2 * nkv) * hd * 2 < (1L << 32) - (1L << 20);
 }
 
-// Linear carve-out of the caller's workspace; every piece 256-byte aligned.
+// Linear carve-out of the caller's workspace; every piece 256-byte aligned.  A null base only counts bytes (the
+// workspace-size queries) and hands out null pointers.
 struct Arena {
     char *base;
     size_t off;
     explicit Arena(void *p) : base((char *)p), off(0) {}
     template <class T = void>
     T *take(size_t bytes) {
-        T *p = (T *)(base + off);
+        T *p = base ? (T *)(base + off) : nullptr;
         off += ms_align_up(bytes);
         return p;
     }
