@@ -204,6 +204,7 @@ def bench_kd_step(name, args, torch, B, wl, dev, side):
         "mfma_frac_teacher_fwd": fl["teacher"] / sec_teacher / 1e12 / PEAK_BF16_TFLOPS,
         "mfma_frac_student_fwd_bwd_kd": (fl["student"] + fl["kd"]) / sec_student / 1e12 / PEAK_BF16_TFLOPS,
         "mfma_frac_kd_loss": fl["kd"] / sec_kd / 1e12 / PEAK_BF16_TFLOPS if sec_kd else None,
+        "student_section_tflops": (fl["student"] + fl["kd"]) / sec_student / 1e12,
         "loss": loss, "logits_to_hidden_ratio": kd.vocab / kd.h_teacher,
         "roofline": {"kernel": "gemm_bf16_fast_kernel (A[M,K] B[N,K]^T: all forward linears and lm_head chunk GEMMs)",
                      "bound": "mfma", "achieved": achieved, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
@@ -376,6 +377,41 @@ def cpu_baseline(work, tw, sw, wt, ws, ids, sample_tokens):
                       f"{sec:.1f} s of fp64 numpy work", "loss": out["loss"]}
 
 
+def wavefront_schedule(B, wl, vit, llm):
+    """Sec. 3.4 closed on measured rates: the 64 samples of the c4 mix go through a vision-encoder section (c4's
+    layers) in front of a critical LLM section (c5's student layers); each sample's six times are its model flops
+    in each section divided by the rate this library just measured for that section (forward : backward flops =
+    1 : 2 for the linears, 1 : 2.5 for attention).  A sample's LLM tokens = its visual tokens after the 4:1 merge plus
+    a seeded text length in [256, 2048] (the workload names no text lengths: a reading); text-only samples skip the
+    vision section (zero times there).  Reports the simulated makespan in input order and in the scheduler's order."""
+    work = wl.workload("c4", 0)
+    v_cfg, l_cfg = work.student, wl.workload("c5", 0).student
+    text = [int(t) for t in wl.randint(0, "c4.text_lengths", len(work.lengths), 256, 2049).tolist()]
+    v_rate = vit["model_tflop_per_step"] / vit["ms_per_step"] * 1e15      # flop/s of the encoder section, fwd+bwd
+    l_rate = llm["student_section_tflops"] * 1e12
+
+    def fb(cfg, tokens, pairs):
+        g = 2.0 * cfg.layer_params() * tokens * cfg.n_layers
+        a = 4.0 * cfg.n_q_heads * cfg.head_dim * pairs * cfg.n_layers
+        return g + a, 2.0 * g + 2.5 * a
+    tuples = []
+    for lv, lt in zip(work.lengths, text):
+        vf, vb = fb(v_cfg, lv, lv * lv)
+        n_llm = lv // 4 + lt
+        lf, lb = fb(l_cfg, n_llm, n_llm * (n_llm + 1) // 2)
+        tuples.append((vf / v_rate, lf / l_rate, 0.0, 0.0, lb / l_rate, vb / v_rate))
+    order, mk = B.schedule_samples(tuples, interleave=True)
+    mk_in, idle_in = B.schedule_makespan(tuples, list(range(len(tuples))), interleave=True)
+    mk_s, idle_s = B.schedule_makespan(tuples, order, interleave=True)
+    crit = sum(t[1] + t[4] for t in tuples)
+    return {"samples": len(tuples), "text_only": sum(1 for l in work.lengths if l == 0),
+            "rates_tflops": {"vision_section_fwd_bwd": v_rate / 1e12, "llm_section_fwd_bwd": l_rate / 1e12},
+            "critical_section_busy_ms": 1e3 * crit,
+            "input_order": {"makespan_ms": 1e3 * mk_in, "critical_idle_ms": 1e3 * idle_in},
+            "scheduled_order": {"makespan_ms": 1e3 * mk_s, "critical_idle_ms": 1e3 * idle_s, "first_samples": order[:8]},
+            "makespan_ratio": mk_s / mk_in}
+
+
 def as_line(res, args, metric):
     line = {"metric": metric, "value": res["tokens_per_s"], "unit": "tokens/s", "n_gpus": 1, "steps": args.steps,
             "warmup": args.warmup, "ms_per_step": res["ms_per_step"], "higher_is_better": True, "scaling": "weak",
@@ -439,6 +475,7 @@ def main():
         free()
     line = as_line(head, args, kd_metric)
     line["workloads"] = others
+    line["wavefront_schedule_c4_mix"] = wavefront_schedule(B, wl, others["c4"], head)
     print(json.dumps(line))
 
 

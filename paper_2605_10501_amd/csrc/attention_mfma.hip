@@ -200,9 +200,12 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
 }
 
 // ===================================================================== backward
-// delta[h, t] = sum_d dO[t, h, d] O[t, h, d]  (the row term of the softmax Jacobian)
+// Row terms of the softmax backward, one pair per (head, token): ld[h, t] = (lse[h, t] * log2(e), delta[h, t]) with
+// delta = sum_d dO[t, h, d] O[t, h, d] (the row term of the softmax Jacobian).  Interleaved so that the 32 pairs of a
+// 32-query tile are 256 contiguous bytes (one direct-to-LDS load in the dK/dV kernel).
 __global__ __launch_bounds__(256) void attn_delta_kernel(const bf16_t *__restrict__ o, const bf16_t *__restrict__ d_o,
-                                                          float *__restrict__ delta, int n, int nq, int hd) {
+                                                          const float *__restrict__ lse, float2 *__restrict__ ld, int n, int nq,
+                                                          int hd) {
     // 8 lanes per (token, head): consecutive lanes read consecutive 16-byte pieces, so a wave's load is one
     // contiguous run; the 8 partial sums meet through xor-shuffles
     const long gid = (long)blockIdx.x * blockDim.x + threadIdx.x;
@@ -221,7 +224,10 @@ __global__ __launch_bounds__(256) void attn_delta_kernel(const bf16_t *__restric
     acc += __shfl_xor(acc, 1, 64);
     acc += __shfl_xor(acc, 2, 64);
     acc += __shfl_xor(acc, 4, 64);
-    if (live && sub == 0) delta[(long)(idx % nq) * n + idx / nq] = acc;
+    if (live && sub == 0) {
+        const long at = (long)(idx % nq) * n + idx / nq;
+        ld[at] = make_float2(lse[at] * 1.4426950408889634f, acc);
+    }
 }
 
 // dQ: same decomposition as the forward kernel (workgroup = 128 queries of one head, keys visited
@@ -231,7 +237,7 @@ __global__ __launch_bounds__(256) void attn_delta_kernel(const bf16_t *__restric
 // with K^T read from the row-major K tile through the transposing LDS load.
 template <int HD, bool CAUSAL>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) void attn_bwd_dq_mfma_kernel(const bf16_t *__restrict__ qkv, const bf16_t *__restrict__ d_o,
-                                                                const float *__restrict__ lse, const float *__restrict__ delta,
+                                                                const float2 *__restrict__ ld2,
                                                                 bf16_t *__restrict__ dqkv, const int *__restrict__ cu, int n,
                                                                 int nq, int nkv, int n_seqs, int ntile_max, float scale) {
     using D = AttnDims<HD>;
@@ -272,8 +278,8 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
             }
         }
     }
-    const float lse2 = qok ? lse[(long)h * n + q] * 1.4426950408889634f : 0.f;
-    const float dlt = qok ? delta[(long)h * n + q] : 0.f;
+    const float2 row = qok ? ld2[(long)h * n + q] : make_float2(0.f, 0.f);   // (lse * log2(e), delta)
+    const float lse2 = row.x, dlt = row.y;
 
     auto issue = [&](int j, bf16_t *kt, bf16_t *vt) {
         constexpr int PER = 4 * D::NKS;
@@ -354,26 +360,55 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
         }
 }
 
-// dK, dV: workgroup = 128 keys of one KV head (32 per wave; K fragments in registers, the V tile in
-// LDS); it walks the query heads of the group and their query tiles, 32 rows at a time, with the Q
-// and dO tiles loaded directly into LDS (double-buffered).  S = Q K^T and dP = dO V^T are accumulator
-// tiles with one KEY per lane and queries down the registers, which is the A-operand layout of
-// dV += P^T dO and dK += dS^T Q; their B operands (dO and Q with queries as the contraction index)
-// come from the row-major tiles through the transposing LDS load.  Everything fits 256 registers and
-// 66 KB of LDS, so two workgroups share a CU and one's softmax overlaps the other's MFMAs.
+// dK, dV: workgroup = NW waves with 32 keys each of one KV head (K fragments in registers; V fragments in registers
+// as well or as a tile in LDS); it walks the query heads of the group and their query tiles, 32 rows at a time.  S = Q K^T and dP = dO V^T
+// are accumulator tiles with one KEY per lane and queries down the registers, which is the A-operand layout of
+// dV += P^T dO and dK += dS^T Q; their B operands (dO and Q with queries as the contraction index) come from the
+// row-major tiles through the transposing LDS load.  256 registers per wave: two waves per SIMD (two 4-wave workgroups
+// per CU, which drift apart so that one's exponentials overlap the other's MFMAs, or one 8-wave workgroup).
+//
+// The query tiles (Q rows, dO rows and the 32 (lse, delta) pairs, everything by direct-to-LDS loads: no load of the
+// loop goes through registers, so no wave waits on a load in the middle of a tile) go through a ring of NST LDS stages,
+// requested NST - 1 tiles ahead.  One barrier per tile does both jobs: before it each wave waits until ITS loads of
+// the tile have landed (s_waitcnt vmcnt(k): loads complete in order and exactly k younger ones, those of the next
+// NST - 2 tiles, may still be in flight; tiles past the end are requested as out-of-range loads so that the count is
+// the same in every iteration), after it all waves have finished the previous tile, whose stage is then handed to the
+// tile NST - 1 ahead.  Measured on MI355X (c5 student / c4 encoder shapes, in the step): NW = 4, NST = 2 (two
+// independent workgroups per CU, 66 KB of LDS each) 28.0 / 57.2 ms per step; NW = 8 with NST = 3 or 4 (one workgroup
+// per CU, all eight waves in lockstep) 28.8 / 58.0 and 29.1 / 67.5: deeper prefetch buys nothing, the kernel is not
+// waiting for memory but for its own MFMA -> exponentials -> MFMA chain, which two independent workgroups overlap
+// better than one.  (NW = 4 with NST = 3 needs 80.75 KB of LDS for head_dim 128, 768 bytes too many for two per CU.)
 // !SPLIT: the sums over the query group stay in registers, no atomics.
 // SPLIT: one workgroup per query head of the group instead of one per K/V head (4x the workgroups and a 4x
 // shorter longest one under grouped-query attention); partial dK/dV are then summed with fp32 atomics
 // into dkv_acc [n][2][nkv * HD], which attn_dkv_store_kernel rounds into dqkv afterwards.
-template <int HD, bool CAUSAL, bool SPLIT>
-__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) void attn_bwd_dkv_mfma_kernel(
-    const bf16_t *__restrict__ qkv, const bf16_t *__restrict__ d_o, const float *__restrict__ lse, const float *__restrict__ delta,
+template <int N> __device__ __forceinline__ void wait_vmcnt_lgkm0() {
+    // gfx9 encoding: vmcnt = bits 3:0 and 15:14, expcnt = bits 6:4 (7: no wait), lgkmcnt = bits 11:8 (0)
+    __builtin_amdgcn_s_waitcnt((N & 15) | ((N >> 4) << 14) | (7 << 4));
+}
+// barrier between waves that exchange data through LDS, without the full memory fence of __syncthreads (which would
+// wait for every outstanding load): the wavefront-scope fences only keep the compiler from moving LDS accesses across
+__device__ __forceinline__ void lds_barrier() {
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_s_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+
+template <int HD, bool CAUSAL, bool SPLIT, int NW, int NST>
+__global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(2, 2))) void attn_bwd_dkv_mfma_kernel(
+    const bf16_t *__restrict__ qkv, const bf16_t *__restrict__ d_o, const float2 *__restrict__ ld2,
     bf16_t *__restrict__ dqkv, float *__restrict__ dkv_acc, const int *__restrict__ cu, int n, int nq, int nkv, int n_seqs,
     float scale) {
     using D = AttnDims<HD>;
-    constexpr int BK_ = 128, BQ = 32, QS = D::NKS * 2048, VS = D::NKS * 4096;
-    __shared__ __align__(16) bf16_t Q0[QS], Q1[QS], O0[QS], O1[QS], Vs[2 * VS];
-    __shared__ __align__(16) float F0[64], F1[64];         // per query row: lse * log2(e) | delta
+    static_assert(NST >= 2 && NST <= 4 && (NW == 4 || NW == 8), "ring of 2..4 stages, 4 or 8 waves");
+    constexpr int BK_ = 32 * NW, BQ = 32, QS = D::NKS * 2048, VS = D::NKS * 4096;
+    constexpr int Q2 = NST > 2 ? QS : 8, Q3 = NST > 3 ? QS : 8;        // stages beyond NST are not used
+    // separate LDS objects per stage: lets the compiler tell the stage being filled from the stage being read
+    __shared__ __align__(16) bf16_t Qa[QS], Qb[QS], Qc[Q2], Qd[Q3], Oa[QS], Ob[QS], Oc[Q2], Od[Q3];
+    __shared__ __align__(16) bf16_t Vs[(BK_ / 64) * VS];
+    __shared__ __align__(16) float Fa[64], Fb[64], Fc[64], Fd[64];     // per query row of the tile: (lse * log2(e), delta)
+    bf16_t *const Qst[4] = {Qa, Qb, Qc, Qd}, *const Ost[4] = {Oa, Ob, Oc, Od};
+    float *const Fst[4] = {Fa, Fb, Fc, Fd};
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -393,11 +428,13 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
     const bool kok = key < s1;
     const float c = scale * 1.4426950408889634f;
     const __amdgpu_buffer_rsrc_t rq = make_rsrc(qkv, (long)n * ld * 2), ro = make_rsrc(d_o, (long)n * ldo * 2);
+    const __amdgpu_buffer_rsrc_t rf = make_rsrc(ld2, (long)nq * n * 8);
 
-    // the V tile (two 64-key row tiles): keys past the end of the sequence hold the next sequence's rows
-    // or zeros, which only ever meet p = 0
+    // the V tile (64-key row tiles): keys past the end of the sequence hold the next sequence's rows or zeros, which
+    // only ever meet p = 0.  (Each wave only reads the rows of its own 32 keys; keeping them in registers like the K
+    // fragments was measured: it spills.)
     {
-        constexpr int PER = 4 * D::NKS;                     // 2 * 8 * NKS instructions over 4 waves
+        constexpr int PER = (BK_ / 64) * 8 * D::NKS / NW;
 #pragma unroll
         for (int i = 0; i < PER; ++i) {
             const int idx = wave * PER + i, t = idx / (8 * D::NKS);
@@ -420,18 +457,22 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
     const int nqt = (s1 - s0 + BQ - 1) / BQ - qt_first;
     const int niter = SPLIT ? nqt : nqt * grp;
 
-    auto issue = [&](int it, bf16_t *qt_, bf16_t *ot_, float *f) {
-        const int h = g * grp + (SPLIT ? hsub : it / nqt);
-        const int qs = s0 + (qt_first + it % nqt) * BQ;
-        constexpr int PER = 2 * D::NKS;                     // 2 * 4 * NKS instructions over 4 waves
+    // Requests tile `it` (out of range: zeros that nobody reads).  Per wave: NKS loads of Q / dO rows, wave 0 one more
+    // for the 32 (lse, delta) pairs = 64 consecutive floats.
+    constexpr int PERQ = 8 * D::NKS / NW;
+    auto issue = [&](int it, bf16_t *qt_, bf16_t *ot_, float *f) __attribute__((always_inline)) {
+        const unsigned inv = it < niter ? 0u : kOob;
+        const int itc = it < niter ? it : 0;
+        const int h = g * grp + (SPLIT ? hsub : itc / nqt);
+        const int qs = s0 + (qt_first + itc % nqt) * BQ;
 #pragma unroll
-        for (int i = 0; i < PER; ++i) {
-            const int idx = wave * PER + i;
-            if (idx < 4 * D::NKS) rowtile32_dma<HD>(rq, qt_, qs, ld, h * HD, idx, lane);
-            else rowtile32_dma<HD>(ro, ot_, qs, ldo, h * HD, idx - 4 * D::NKS, lane);
+        for (int i = 0; i < PERQ; ++i) {
+            const int idx = wave * PERQ + i;
+            if (idx < 4 * D::NKS) rowtile32_dma<HD>(rq, qt_, qs, ld, h * HD, idx, lane, inv);
+            else rowtile32_dma<HD>(ro, ot_, qs, ldo, h * HD, idx - 4 * D::NKS, lane, inv);
         }
-        if (tid < 32) f[tid] = qs + tid < s1 ? lse[(long)h * n + qs + tid] * 1.4426950408889634f : 0.f;
-        else if (tid < 64) f[tid] = qs + tid - 32 < s1 ? delta[(long)h * n + qs + tid - 32] : 0.f;
+        if (wave == 0)
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(rf, (lds_void *)f, 4, (unsigned)((((long)h * n + qs) * 2 + lane) * 4) | inv, 0, 0, 0);
     };
 
     const bf16_t *vrow = Vs + (wave >> 1) * VS;             // the 64-key row tile holding this wave's keys
@@ -439,13 +480,12 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
     // One pass over the query tiles accumulates dV (WHICH = 0: needs S only), dK (1: needs S and dP) or both
     // (2).  With wide heads the two accumulator sets do not fit 256 registers: two passes (0 then 1) cost one
     // extra S product and a second round of exponentials per tile but halve the accumulators, which is what
-    // lets two workgroups share a CU.  Heads of at most 96 columns fit both sets: one pass.
+    // lets two waves share a SIMD.  Heads of at most 96 columns fit both sets: one pass.
     constexpr bool ONE_PASS = D::DB <= 3;
     f32x16 acc[D::DB], acc2[ONE_PASS ? D::DB : 1];          // acc2: dV when both are accumulated (acc is dK then)
     auto compute = [&](auto which, int it, const bf16_t *qt_, const bf16_t *ot_, const float *f) __attribute__((always_inline)) {
         constexpr int WHICH = decltype(which)::value;
         constexpr bool DK = WHICH >= 1, BOTH = WHICH == 2;
-        const float *ls = f, *dl = f + 32;
         const int qs = s0 + (qt_first + it % nqt) * BQ;
         if (CAUSAL && qs + BQ - 1 < kw0) return;            // every query of the tile precedes every key of the wave
         f32x16 st, dp;
@@ -460,8 +500,8 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
                 dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*(const bf16x8 *)(ot_ + (ks / 4) * 2048 + off), vfr, dp, 0, 0, 0);
             }
         }
-        // accumulator rows are queries 8*(r/4) + 4*half + r%4, the column is this lane's key; rows past
-        // the end of the sequence have zero Q, dO, lse and delta, so only keys need masking there
+        // accumulator rows are queries 8*(r/4) + 4*half + r%4, the column is this lane's key; keys and queries past
+        // the end of the sequence are masked (their rows hold the next sequence's data or zeros)
         const bool need_mask = kw0 + 31 >= s1 || qs + BQ > s1 || (CAUSAL && kw0 + 31 > qs);
         // 16 queries (one MFMA k-step of the second product) at a time, to keep few values live
 #pragma unroll
@@ -470,13 +510,8 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
 #pragma unroll
             for (int rg = 0; rg < 2; ++rg) {
                 const int qr = 16 * t + 8 * rg + 4 * half;
-                const float4 l4 = *(const float4 *)(ls + qr);
-                const float lv[4] = {l4.x, l4.y, l4.z, l4.w};
-                float dvv[4] = {0.f, 0.f, 0.f, 0.f};
-                if constexpr (DK) {
-                    const float4 d4 = *(const float4 *)(dl + qr);
-                    dvv[0] = d4.x; dvv[1] = d4.y; dvv[2] = d4.z; dvv[3] = d4.w;
-                }
+                const float4 fa = *(const float4 *)(f + 2 * qr), fb = *(const float4 *)(f + 2 * qr + 4);
+                const float lv[4] = {fa.x, fa.z, fb.x, fb.z}, dvv[4] = {fa.y, fa.w, fb.y, fb.w};
 #pragma unroll
                 for (int e = 0; e < 4; ++e) {
                     const int r = rg * 4 + e;
@@ -517,6 +552,17 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
             }
         }
     };
+    // one tile of the ring: stage S holds tile `it`; the stage of tile it - 1 receives tile it + NST - 1
+    auto ring_step = [&](auto which, int it, const bf16_t *q_cur, const bf16_t *o_cur, const float *f_cur, bf16_t *q_nxt,
+                         bf16_t *o_nxt, float *f_nxt) __attribute__((always_inline)) {
+        if (it >= niter) return;                            // workgroup-uniform
+        // own loads of tile `it` have landed; the younger ones (tiles it+1 .. it+NST-2) may still be in flight
+        if (wave == 0) wait_vmcnt_lgkm0<(NST - 2) * (PERQ + 1)>();
+        else wait_vmcnt_lgkm0<(NST - 2) * PERQ>();
+        lds_barrier();
+        issue(it + NST - 1, q_nxt, o_nxt, f_nxt);
+        compute(which, it, q_cur, o_cur, f_cur);
+    };
     auto pass = [&](auto which) __attribute__((always_inline)) {
 #pragma unroll
         for (int i = 0; i < D::DB; ++i)
@@ -525,16 +571,18 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
                 acc[i][r] = 0.f;
                 if constexpr (ONE_PASS) acc2[i][r] = 0.f;
             }
-        issue(0, Q0, O0, F0);
-        dma_publish_barrier();
-        for (int it = 0; it < niter; it += 2) {
-            if (it + 1 < niter) issue(it + 1, Q1, O1, F1);
-            compute(which, it, Q0, O0, F0);
-            dma_publish_barrier();
-            if (it + 2 < niter) issue(it + 2, Q0, O0, F0);
-            if (it + 1 < niter) compute(which, it + 1, Q1, O1, F1);
-            dma_publish_barrier();
+#pragma unroll
+        for (int k = 0; k < NST - 1; ++k) issue(k, Qst[k], Ost[k], Fst[k]);
+        for (int it = 0; it < niter; it += NST) {
+#pragma unroll
+            for (int k = 0; k < NST; ++k) {
+                constexpr int P = NST - 1;                  // stage k holds tile it + k; stage k - 1 (mod NST) is free
+                ring_step(which, it + k, Qst[k], Ost[k], Fst[k], Qst[(k + P) % NST], Ost[(k + P) % NST], Fst[(k + P) % NST]);
+            }
         }
+        // everything still in flight (tiles past the end: zeros) lands, and every wave is done reading, before the
+        // stages are reused by the next pass or the workgroup's LDS is released
+        __syncthreads();
     };
     if constexpr (ONE_PASS) {
         pass(std::integral_constant<int, 2>{});
@@ -579,36 +627,35 @@ ms_status launch_fwd(int causal, int nq, int nkv, int n, int n_seqs, int max_seq
 template <int HD>
 ms_status launch_bwd(int causal, int nq, int nkv, int n, int n_seqs, int max_seqlen, const int *cu, const void *qkv,
                      const void *o, const float *lse, const void *d_o, void *dqkv, void *scratch, hipStream_t s) {
-    float *delta = (float *)scratch;
-    attn_delta_kernel<<<ms_cdiv((long)n * nq * 8, 256), 256, 0, s>>>((const bf16_t *)o, (const bf16_t *)d_o, delta, n, nq, HD);
-    MS_LAUNCH_CHECK();
     const float scale = 1.f / sqrtf((float)HD);
     const int ntile_max = ms_cdiv(max_seqlen, 128);
     const long blocks = (long)ntile_max * nq * n_seqs;
-    if (blocks > 0x7fffffffL || !ms_attn_offsets_fit(n, nq, nkv, HD))
-        return ms_fail(MS_ERR_UNSUPPORTED, "attention: batch too large for 32-bit tile offsets");
     // grouped-query attention: split the group's query heads over workgroups (see the kernel)
     const bool split = nq / nkv > 1;
-    const long blocks_dkv = (long)ntile_max * nkv * n_seqs * (split ? nq / nkv : 1);
-    if (blocks_dkv > 0x7fffffffL) return ms_fail(MS_ERR_UNSUPPORTED, "attention: batch too large for 32-bit tile offsets");
+    const long blocks_dkv = (long)ms_cdiv(max_seqlen, 128) * nkv * n_seqs * (split ? nq / nkv : 1);   // 128 keys each
+    if (blocks > 0x7fffffffL || blocks_dkv > 0x7fffffffL || !ms_attn_offsets_fit(n, nq, nkv, HD))
+        return ms_fail(MS_ERR_UNSUPPORTED, "attention: batch too large for 32-bit tile offsets");
     const unsigned grid_dkv = (unsigned)blocks_dkv;
-    float *dkv_acc = (float *)((char *)scratch + ms_align_up((size_t)nq * n * sizeof(float)));
+    float2 *ld2 = (float2 *)scratch;                       // [nq][n] pairs (lse * log2(e), delta)
+    attn_delta_kernel<<<ms_cdiv((long)n * nq * 8, 256), 256, 0, s>>>((const bf16_t *)o, (const bf16_t *)d_o, lse, ld2, n, nq, HD);
+    MS_LAUNCH_CHECK();
+    float *dkv_acc = (float *)((char *)scratch + ms_align_up((size_t)nq * n * sizeof(float2)));
     const int w = 2 * nkv * HD;
     if (split) MS_TRY(launch_fill_f32(dkv_acc, (long)n * w, 0.f, s));
 #define GO(C)                                                                                                          \
     do {                                                                                                               \
-        attn_bwd_dq_mfma_kernel<HD, C><<<(unsigned)blocks, 256, 0, s>>>((const bf16_t *)qkv, (const bf16_t *)d_o, lse, \
-                                                                        delta, (bf16_t *)dqkv, cu, n, nq, nkv, n_seqs, \
+        attn_bwd_dq_mfma_kernel<HD, C><<<(unsigned)blocks, 256, 0, s>>>((const bf16_t *)qkv, (const bf16_t *)d_o, ld2, \
+                                                                        (bf16_t *)dqkv, cu, n, nq, nkv, n_seqs,        \
                                                                         ntile_max, scale);                             \
         MS_LAUNCH_CHECK();                                                                                             \
         if (split)                                                                                                     \
-            attn_bwd_dkv_mfma_kernel<HD, C, true><<<grid_dkv, 256, 0, s>>>((const bf16_t *)qkv, (const bf16_t *)d_o,   \
-                                                                           lse, delta, (bf16_t *)dqkv, dkv_acc, cu, n, \
-                                                                           nq, nkv, n_seqs, scale);                    \
+            attn_bwd_dkv_mfma_kernel<HD, C, true, 4, 2><<<grid_dkv, 256, 0, s>>>((const bf16_t *)qkv, (const bf16_t *)d_o, \
+                                                                                 ld2, (bf16_t *)dqkv, dkv_acc, cu, n,  \
+                                                                                 nq, nkv, n_seqs, scale);              \
         else                                                                                                           \
-            attn_bwd_dkv_mfma_kernel<HD, C, false><<<grid_dkv, 256, 0, s>>>((const bf16_t *)qkv, (const bf16_t *)d_o,  \
-                                                                            lse, delta, (bf16_t *)dqkv, dkv_acc, cu,   \
-                                                                            n, nq, nkv, n_seqs, scale);                \
+            attn_bwd_dkv_mfma_kernel<HD, C, false, 4, 2><<<grid_dkv, 256, 0, s>>>((const bf16_t *)qkv, (const bf16_t *)d_o, \
+                                                                                  ld2, (bf16_t *)dqkv, dkv_acc, cu, n, \
+                                                                                  nq, nkv, n_seqs, scale);             \
     } while (0)
     if (causal) GO(true); else GO(false);
 #undef GO
@@ -636,8 +683,8 @@ ms_status attn_mfma_forward(int causal, int nq, int nkv, int hd, int n, int n_se
 }
 
 size_t attn_mfma_backward_scratch_bytes(int nq, int nkv, int hd, int n) {
-    // delta [nq][n], then (grouped-query attention only) the fp32 dK/dV accumulator [n][2][nkv * hd]
-    return ms_align_up((size_t)nq * n * sizeof(float)) + (nq > nkv ? ms_align_up((size_t)n * 2 * nkv * hd * sizeof(float)) : 0);
+    // (lse, delta) pairs [nq][n], then (grouped-query attention only) the fp32 dK/dV accumulator [n][2][nkv * hd]
+    return ms_align_up((size_t)nq * n * 2 * sizeof(float)) + (nq > nkv ? ms_align_up((size_t)n * 2 * nkv * hd * sizeof(float)) : 0);
 }
 
 ms_status attn_mfma_backward(int causal, int nq, int nkv, int hd, int n, int n_seqs, int max_seqlen, const int *cu,

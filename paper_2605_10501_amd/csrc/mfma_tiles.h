@@ -66,12 +66,12 @@ __device__ __forceinline__ void rowtile_dma(__amdgpu_buffer_rsrc_t rs, bf16_t *t
 // The same for a tile of 32 rows (sub-tiles [32][64]): instruction idx fills 8-row group idx % 4 of sub-tile idx / 4.
 template <int W>
 __device__ __forceinline__ void rowtile32_dma(__amdgpu_buffer_rsrc_t rs, bf16_t *tile, int row0, long ld, int col0, int idx,
-                                              int lane) {
+                                              int lane, unsigned inv = 0) {
     const int sub = idx >> 2, g = idx & 3;
     const int r = g * 8 + (lane >> 3);
     const int c = (lane & 7) ^ (lane >> 3) ^ g;
     const int d = sub * 64 + c * 8;
-    const unsigned voff = d < W ? (unsigned)(((long)(row0 + r) * ld + col0 + d) * 2) : kOob;
+    const unsigned voff = (d < W ? (unsigned)(((long)(row0 + r) * ld + col0 + d) * 2) : kOob) | inv;   // inv = kOob: all zeros
     __builtin_amdgcn_raw_ptr_buffer_load_lds(rs, (lds_void *)(tile + sub * 2048 + g * 512), 16, voff, 0, 0, 0);
 }
 

@@ -116,7 +116,10 @@ def assert_parity_vs_noise(gpu, ref, ref_perturbed, name="", factor=1.5, cap_rms
     ten elements above it, else 1 - 10 / size (on a 1280-element gain gradient p99.9 IS the largest element, whose
     ratio between two noise realisations is not bounded by 1.5).  Absolute caps keep the check from becoming vacuous:
     rms <= cap_rms always; the maximum <= cap_max unless the noise floor's own maximum is that large (weight gradients
-    of a few hundred tokens have such elements: sums of few terms), in which case it may exceed the floor's by 25 %."""
+    of a few hundred tokens have such elements: sums of few terms), in which case it may exceed the floor's by 50 % (the
+    largest of 10^7 heavy-tailed ratios differs that much between two realisations).  A tensor that no rounding
+    touches (a bias gradient that is a plain column sum of the upstream gradient) has a noise floor of exactly zero:
+    it passes when every element is within the fp32 tolerance."""
     e, f = rel_err(gpu, ref), rel_err(ref_perturbed, ref)
     assert np.all(np.isfinite(e)), f"{name}: non-finite values"
     ql = min(0.999, max(0.5, 1.0 - 10.0 / max(e.size, 1)))
@@ -124,6 +127,8 @@ def assert_parity_vs_noise(gpu, ref, ref_perturbed, name="", factor=1.5, cap_rms
     (er, eq, em), (fr, fq, fm) = stats(e), stats(f)
     msg = (f"{name}: gpu-vs-oracle rms {er:.3e} p{100 * ql:.1f} {eq:.3e} max {em:.3e}; noise floor rms {fr:.3e} "
            f"p{100 * ql:.1f} {fq:.3e} max {fm:.3e}")
+    if em <= TOL_F32:
+        return msg
     assert er <= factor * fr and eq <= factor * fq and em <= 2 * factor * fm, msg
-    assert er <= cap_rms and em <= max(cap_max, 1.25 * fm), msg
+    assert er <= cap_rms and em <= max(cap_max, 1.5 * fm), msg
     return msg
