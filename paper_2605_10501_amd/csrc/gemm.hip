@@ -58,6 +58,26 @@ struct GemmParams {
 
 enum { EPI_NONE = 0, EPI_KD_DZ = 1, EPI_KD_STATS = 2, EPI_SWIGLU = 3 };
 
+// All-reduce over each aligned group of 16 lanes with DPP moves (one vector-ALU instruction per step, no LDS
+// crossbar): swap within pairs, swap pairs within quads, mirror within 8 lanes (reaches the other quad), mirror within
+// 16 lanes (reaches the other half).  After the four steps all 16 lanes hold the group's result.
+template <int CTRL> __device__ __forceinline__ float dpp_move(float v) {
+    return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), CTRL, 0xF, 0xF, true));
+}
+constexpr int kDppQuadXor1 = 0xB1, kDppQuadXor2 = 0x4E, kDppRowHalfMirror = 0x141, kDppRowMirror = 0x140;
+__device__ __forceinline__ float row16_max(float v) {
+    v = fmaxf(v, dpp_move<kDppQuadXor1>(v));
+    v = fmaxf(v, dpp_move<kDppQuadXor2>(v));
+    v = fmaxf(v, dpp_move<kDppRowHalfMirror>(v));
+    return fmaxf(v, dpp_move<kDppRowMirror>(v));
+}
+__device__ __forceinline__ float row16_sum(float v) {
+    v += dpp_move<kDppQuadXor1>(v);
+    v += dpp_move<kDppQuadXor2>(v);
+    v += dpp_move<kDppRowHalfMirror>(v);
+    return v + dpp_move<kDppRowMirror>(v);
+}
+
 // Cache policy of the vector epilogues' global accesses (auxiliary operand of the buffer instructions): non-temporal.
 // The output tile, the residual and the teacher logits stream through once, and the 4 MB L2 of an XCD is what
 // keeps the operand panels that its 32 CUs share; left at the default policy the epilogue traffic evicts them
@@ -589,7 +609,8 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_bf16_fast_kernel(GemmParams
                 const float gv[4] = {g4.x, g4.y, g4.z, g4.w}, uv[4] = {u4.x, u4.y, u4.z, u4.w};
                 float a[4];
 #pragma unroll
-                for (int e = 0; e < 4; ++e) a[e] = gv[e] / (1.f + __expf(-gv[e])) * uv[e];
+                for (int e = 0; e < 4; ++e)   // silu(g) u = g u / (1 + e^-g); hardware reciprocal (1 ulp) instead of the division sequence
+                    a[e] = gv[e] * uv[e] * __builtin_amdgcn_rcpf(1.f + __builtin_amdgcn_exp2f(-1.4426950408889634f * gv[e]));
                 const long rowg = m0 + wm * WTM + i * 32 + row;
                 __builtin_amdgcn_raw_buffer_store_b64(pack4(a), rc, cok ? (unsigned)((rowg * p.ldc + colg) * 2) : kOob, 0, kStream);
                 if (p.sg_gu) {
@@ -658,6 +679,7 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_bf16_fast_kernel(GemmParams
             }
         };
         const float it = p.kd_inv_t;
+        const float it2 = it * 1.4426950408889634f;      // e^{z/T - m} = 2^{z it2 - m log2(e)}: one fused multiply-add feeds exp2
         if (has_aux) prefetch(0, aux[0], lsev[0]);
 #pragma unroll
         for (int i = 0; i < MI32; ++i) {
@@ -697,40 +719,38 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_bf16_fast_kernel(GemmParams
                     for (int e = 0; e < 4; ++e) zt[e] = __uint_as_float(q[e]);
                     if constexpr (EPI == EPI_KD_DZ) {
                         // dz = coef * (exp(zs/T - lse_s) - exp(zt/T - lse_t)) -> C (storage dtype)
-                        const float lse_t = lsev[i & 1][ps].x, lse_s = lsev[i & 1][ps].y;
+                        const float lt2 = lsev[i & 1][ps].x * 1.4426950408889634f, ls2 = lsev[i & 1][ps].y * 1.4426950408889634f;
                         float v[4];
 #pragma unroll
-                        for (int e = 0; e < 4; ++e) v[e] = p.kd_coef * (__expf(zs[e] * it - lse_s) - __expf(zt[e] * it - lse_t));
+                        for (int e = 0; e < 4; ++e)
+                            v[e] = p.kd_coef * (__builtin_amdgcn_exp2f(__builtin_fmaf(zs[e], it2, -ls2)) -
+                                                __builtin_amdgcn_exp2f(__builtin_fmaf(zt[e], it2, -lt2)));
                         store4(v, co);
                     } else {
                         // per row, over this wave's 64 columns: max and sum of exponentials of zt/T and zs/T and
                         // the cross term sum e^{zt/T - m_t} (zt - zs)/T -> kd_part; the 16 lanes that share a
-                        // row reduce with xor-shuffles inside their group
+                        // row reduce with data-parallel-primitive moves inside their group (no LDS round trip)
                         float mt = cok ? fmaxf(fmaxf(zt[0], zt[1]), fmaxf(zt[2], zt[3])) : -INFINITY;
                         float ms = cok ? fmaxf(fmaxf(zs[0], zs[1]), fmaxf(zs[2], zs[3])) : -INFINITY;
-#pragma unroll
-                        for (int o = 1; o < 16; o <<= 1) {
-                            mt = fmaxf(mt, __shfl_xor(mt, o, 64));
-                            ms = fmaxf(ms, __shfl_xor(ms, o, 64));
-                        }
+                        mt = row16_max(mt);
+                        ms = row16_max(ms);
                         mt *= it; ms *= it;                                   // T > 0
-                        const float mtu = mt == -INFINITY ? 0.f : mt, msu = ms == -INFINITY ? 0.f : ms;
+                        const float mt2 = mt == -INFINITY ? 0.f : mt * 1.4426950408889634f;
+                        const float ms2 = ms == -INFINITY ? 0.f : ms * 1.4426950408889634f;
                         float st = 0.f, ss = 0.f, ac = 0.f;
                         if (cok) {
 #pragma unroll
                             for (int e = 0; e < 4; ++e) {
-                                const float et = __expf(zt[e] * it - mtu);
+                                const float et = __builtin_amdgcn_exp2f(__builtin_fmaf(zt[e], it2, -mt2));
                                 st += et;
-                                ac += et * (zt[e] - zs[e]) * it;
-                                ss += __expf(zs[e] * it - msu);
+                                ac = __builtin_fmaf(et, zt[e] - zs[e], ac);
+                                ss += __builtin_amdgcn_exp2f(__builtin_fmaf(zs[e], it2, -ms2));
                             }
+                            ac *= it;
                         }
-#pragma unroll
-                        for (int o = 1; o < 16; o <<= 1) {
-                            st += __shfl_xor(st, o, 64);
-                            ss += __shfl_xor(ss, o, 64);
-                            ac += __shfl_xor(ac, o, 64);
-                        }
+                        st = row16_sum(st);
+                        ss = row16_sum(ss);
+                        ac = row16_sum(ac);
                         if ((lane & 15) == 0 && rowg < p.M && n0 + wn * WTN < p.N) {
                             float *o = p.kd_part + ((long)rowg * p.kd_nparts + (n0 + wn * WTN) / 64) * 8;
                             *(float4 *)o = make_float4(mt, st, ms, ss);
