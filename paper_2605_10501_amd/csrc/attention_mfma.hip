@@ -30,6 +30,35 @@ __device__ __forceinline__ bf16x8 pack8(const float *v) {
     return r;
 }
 
+// Workgroup -> (sequence, head, tile level).  Workgroups reach the 8 XCDs round-robin by blockIdx, and each XCD has an
+// L2 of its own: XCD k runs the blocks with blockIdx % 8 == k, in blockIdx order.  The heads are divided into
+// G = gcd(heads, 8) classes of hpc neighbouring heads (one GQA group or a part of one); a class belongs to S = 8 / G
+// XCDs, which stripe its tile levels between them in serpentine order, so that under a causal mask every stripe weighs
+// the same whatever the sequence lengths are.  Level 0 is the heaviest tile (the last query tile, the first key
+// block).  Within an XCD the order is chunks of kAttnChunk levels, heaviest chunk first, and within a chunk sequence,
+// head of the class, level: the workgroups that run at one time are neighbouring levels of a few (sequence, head)
+// pairs and read the same K/V (or Q/dO) rows, which then come from L2.
+constexpr int kAttnChunk = 8;
+struct AttnGrid { int S, hpc, M; long blocks; };
+__host__ __device__ inline AttnGrid attn_grid(int heads, int n_seqs, int nlevel_max) {
+    const int low = heads & -heads, G = low < 8 ? low : 8;          // gcd(heads, 8)
+    AttnGrid a;
+    a.S = 8 / G; a.hpc = heads / G;
+    a.M = ((nlevel_max + a.S - 1) / a.S + kAttnChunk - 1) / kAttnChunk * kAttnChunk;   // levels per stripe, whole chunks
+    a.blocks = 8L * a.M * a.hpc * n_seqs;
+    return a;
+}
+struct AttnSlot { int b, h, level; };
+__device__ inline AttnSlot attn_slot(unsigned bid, int heads, int n_seqs, int nlevel_max) {
+    const AttnGrid a = attn_grid(heads, n_seqs, nlevel_max);
+    const int k = bid & 7, j = bid >> 3;
+    const int cls = k / a.S, r = k % a.S;
+    const int li = j % kAttnChunk, hc = (j / kAttnChunk) % a.hpc;
+    const int b = (j / (kAttnChunk * a.hpc)) % n_seqs, chunk = j / (kAttnChunk * a.hpc * n_seqs);
+    const int m = chunk * kAttnChunk + li, rr = (r + b + hc) % a.S;
+    return {b, cls * a.hpc + hc, m * a.S + ((m & 1) ? a.S - 1 - rr : rr)};
+}
+
 template <int HD, bool CAUSAL>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) void attn_fwd_mfma_kernel(const bf16_t *__restrict__ qkv, bf16_t *__restrict__ o,
                                                              float *__restrict__ lse, const int *__restrict__ cu, int n,
@@ -42,10 +71,9 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int lrow = lane & 31, half = lane >> 5;
-    // heaviest (latest) query tiles of all heads and sequences first
-    const int per = nq * n_seqs;
-    const int qt = ntile_max - 1 - (int)(blockIdx.x / per);
-    const int h = (blockIdx.x % per) % nq, b = (blockIdx.x % per) / nq;
+    const AttnSlot slot = attn_slot(blockIdx.x, nq, n_seqs, ntile_max);
+    const int qt = ntile_max - 1 - slot.level, h = slot.h, b = slot.b;
+    if (qt < 0) return;
     const int s0 = cu[b], s1 = cu[b + 1];
     if (qt * BQ >= s1 - s0) return;
     const int g = h / (nq / nkv);
@@ -247,9 +275,9 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int lrow = lane & 31, half = lane >> 5;
-    const int per = nq * n_seqs;
-    const int qt = ntile_max - 1 - (int)(blockIdx.x / per);
-    const int h = (blockIdx.x % per) % nq, b = (blockIdx.x % per) / nq;
+    const AttnSlot slot = attn_slot(blockIdx.x, nq, n_seqs, ntile_max);
+    const int qt = ntile_max - 1 - slot.level, h = slot.h, b = slot.b;
+    if (qt < 0) return;
     const int s0 = cu[b], s1 = cu[b + 1];
     if (qt * BQ >= s1 - s0) return;
     const int g = h / (nq / nkv);
@@ -398,7 +426,7 @@ template <int HD, bool CAUSAL, bool SPLIT, int NW, int NST>
 __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(2, 2))) void attn_bwd_dkv_mfma_kernel(
     const bf16_t *__restrict__ qkv, const bf16_t *__restrict__ d_o, const float2 *__restrict__ ld2,
     bf16_t *__restrict__ dqkv, float *__restrict__ dkv_acc, const int *__restrict__ cu, int n, int nq, int nkv, int n_seqs,
-    float scale) {
+    int nblk_max, float scale) {
     using D = AttnDims<HD>;
     static_assert(NST >= 2 && NST <= 4 && (NW == 4 || NW == 8), "ring of 2..4 stages, 4 or 8 waves");
     constexpr int BK_ = 32 * NW, BQ = 32, QS = D::NKS * 2048, VS = D::NKS * 4096;
@@ -413,14 +441,13 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(2, 2)))
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int lrow = lane & 31, half = lane >> 5;
-    // earliest key blocks (most query tiles under a causal mask) of all heads and sequences first
+    // level = key block: the earliest key blocks meet the most query tiles under a causal mask
     const int grp = nq / nkv;
-    const int nsub = SPLIT ? grp : 1;
-    const int per = nkv * n_seqs * nsub;
-    const int rem = blockIdx.x % per;
-    const int hsub = rem % nsub, g = (rem / nsub) % nkv, b = rem / (nsub * nkv);
+    const AttnSlot slot = attn_slot(blockIdx.x, SPLIT ? nq : nkv, n_seqs, nblk_max);
+    const int hsub = SPLIT ? slot.h % grp : 0, g = SPLIT ? slot.h / grp : slot.h, b = slot.b;
+    if (slot.level >= nblk_max) return;
     const int s0 = cu[b], s1 = cu[b + 1];
-    const int kblk = (int)(blockIdx.x / per) * BK_;         // first key of the workgroup, relative to s0
+    const int kblk = slot.level * BK_;                      // first key of the workgroup, relative to s0
     if (kblk >= s1 - s0) return;
     const long ld = (long)(nq + 2 * nkv) * HD, ldo = (long)nq * HD;
     const int kw0 = s0 + kblk + wave * 32;                  // first key of the wave
@@ -614,7 +641,7 @@ template <int HD>
 ms_status launch_fwd(int causal, int nq, int nkv, int n, int n_seqs, int max_seqlen, const int *cu, const void *qkv,
                      void *o, float *lse, hipStream_t s) {
     const int ntile_max = ms_cdiv(max_seqlen, 128);
-    const long blocks = (long)ntile_max * nq * n_seqs;
+    const long blocks = attn_grid(nq, n_seqs, ntile_max).blocks;
     if (blocks > 0x7fffffffL || !ms_attn_offsets_fit(n, nq, nkv, HD))
         return ms_fail(MS_ERR_UNSUPPORTED, "attention: batch too large for 32-bit tile offsets");
     const float sc = 1.4426950408889634f / sqrtf((float)HD);
@@ -629,10 +656,10 @@ ms_status launch_bwd(int causal, int nq, int nkv, int n, int n_seqs, int max_seq
                      const void *o, const float *lse, const void *d_o, void *dqkv, void *scratch, hipStream_t s) {
     const float scale = 1.f / sqrtf((float)HD);
     const int ntile_max = ms_cdiv(max_seqlen, 128);
-    const long blocks = (long)ntile_max * nq * n_seqs;
+    const long blocks = attn_grid(nq, n_seqs, ntile_max).blocks;
     // grouped-query attention: split the group's query heads over workgroups (see the kernel)
     const bool split = nq / nkv > 1;
-    const long blocks_dkv = (long)ms_cdiv(max_seqlen, 128) * nkv * n_seqs * (split ? nq / nkv : 1);   // 128 keys each
+    const long blocks_dkv = attn_grid(split ? nq : nkv, n_seqs, ntile_max).blocks;     // 128 keys each, like the query tiles
     if (blocks > 0x7fffffffL || blocks_dkv > 0x7fffffffL || !ms_attn_offsets_fit(n, nq, nkv, HD))
         return ms_fail(MS_ERR_UNSUPPORTED, "attention: batch too large for 32-bit tile offsets");
     const unsigned grid_dkv = (unsigned)blocks_dkv;
@@ -651,11 +678,11 @@ ms_status launch_bwd(int causal, int nq, int nkv, int n, int n_seqs, int max_seq
         if (split)                                                                                                     \
             attn_bwd_dkv_mfma_kernel<HD, C, true, 4, 2><<<grid_dkv, 256, 0, s>>>((const bf16_t *)qkv, (const bf16_t *)d_o, \
                                                                                  ld2, (bf16_t *)dqkv, dkv_acc, cu, n,  \
-                                                                                 nq, nkv, n_seqs, scale);              \
+                                                                                 nq, nkv, n_seqs, ntile_max, scale);   \
         else                                                                                                           \
             attn_bwd_dkv_mfma_kernel<HD, C, false, 4, 2><<<grid_dkv, 256, 0, s>>>((const bf16_t *)qkv, (const bf16_t *)d_o, \
                                                                                   ld2, (bf16_t *)dqkv, dkv_acc, cu, n, \
-                                                                                  nq, nkv, n_seqs, scale);             \
+                                                                                  nq, nkv, n_seqs, ntile_max, scale);  \
     } while (0)
     if (causal) GO(true); else GO(false);
 #undef GO
