@@ -5,7 +5,7 @@
 //     128 x 128 x 64 (4 waves, two per CU); v_mfma_f32_16x16x32_bf16 by default (v_mfma_f32_32x32x16_bf16 selectable);
 //   * every operand tile goes global -> LDS directly (buffer_load ... lds), two LDS buffers per operand, one barrier
 //     per K tile; a K-contiguous operand lands as [rows][64] with the 16-byte chunk index XOR-swizzled (applied on the
-//     global side of the load), a K-major operand (weight gradients, input gradients) lands as a row tile and is read
+//     global side of the load; the swizzle makes every fragment read pattern free of LDS bank conflicts), a K-major operand (weight gradients, input gradients) lands as a row tile and is read
 //     through the transposing LDS load (ds_read_b64_tr_b16), so no layout needs a transposed copy;
 //   * fragments are double-buffered in registers, LDS reads of the next k-step interleaved with the MFMAs;
 //   * epilogues (bias, bf16 / fp32 residual, fp32 or bf16 output, accumulate, fused SwiGLU, fused KD statistics / dz)
@@ -223,7 +223,7 @@ struct RowTileStager {
         for (int i = 0; i < NI; ++i) {
             const int idx = wave * NI + i, sub = idx >> 3, g = idx & 7;
             const int r = g * 8 + (lane >> 3);
-            const int c = (lane & 7) ^ (lane >> 3) ^ (g & 3);
+            const int c = (lane & 7) ^ swz_row(r);
             base[i] = (unsigned)r * ldb + (unsigned)(col0 + sub * 64 + c * 8) * 2;
         }
     }
@@ -250,7 +250,7 @@ struct GateUpStager {
     __device__ __forceinline__ void init(long ld, int col0_, int f_, int lane) {
         ldb = (unsigned)(ld * 2);
         lanepart = (unsigned)(lane >> 3) * ldb;
-        x = (lane & 7) ^ (lane >> 3);
+        x = (lane & 7) ^ swz_row(lane >> 3);
         col0 = col0_;
         f = f_;
     }
@@ -259,7 +259,7 @@ struct GateUpStager {
         for (int i = 0; i < NI; ++i) {
             const int g = wave * NI + i;                                   // 8-row group of the tile (scalar)
             const int wrow = ((g >> 2) & 1) * f + col0 + (g >> 3) * 32 + (g & 3) * 8;
-            const unsigned voff = ((unsigned)wrow * ldb + lanepart + ((x ^ (g & 3)) << 4)) | inv;
+            const unsigned voff = ((unsigned)wrow * ldb + lanepart + ((x ^ swz_row(8 * g)) << 4)) | inv;
             __builtin_amdgcn_raw_ptr_buffer_load_lds(rs, (lds_void *)(tile + g * 8 * BK), 16, voff, k0 * 2, 0, 0);
         }
     }
@@ -270,11 +270,11 @@ struct DmaStager {
     static constexpr int NI = ROWS / 8 / NWAVES;   // instructions per wave per tile
     unsigned rowoff;                       // byte offset of this lane's row within an 8-row group
     unsigned ld8;                          // bytes between 8-row groups
-    int x;                                 // (lane & 7) ^ (lane >> 3): chunk swizzle without the group term (g & 3)
+    int x;                                 // (lane & 7) ^ swz_row(lane >> 3): chunk swizzle without the group term swz_row(8 g)
     __device__ __forceinline__ void init(long ld, int row0, int lane) {
         rowoff = (unsigned)(((long)(row0 + (lane >> 3)) * ld) * 2);
         ld8 = (unsigned)(ld * 16);
-        x = (lane & 7) ^ (lane >> 3);
+        x = (lane & 7) ^ swz_row(lane >> 3);
     }
     // wave (scalar) fills 8-row groups wave*NI .. wave*NI + NI-1 of the tile
     // inv = 0, or kOob to fill the tile with zeros (OR-ing it in puts every lane out of range without a branch)
@@ -282,7 +282,7 @@ struct DmaStager {
 #pragma unroll
         for (int i = 0; i < NI; ++i) {
             const int g = wave * NI + i;
-            const unsigned voff = (rowoff + g * ld8 + ((x ^ (g & 3)) << 4)) | inv;
+            const unsigned voff = (rowoff + g * ld8 + ((x ^ swz_row(8 * g)) << 4)) | inv;
             __builtin_amdgcn_raw_ptr_buffer_load_lds(rs, (lds_void *)(tile + g * 8 * BK), 16, voff, k0 * 2, 0, 0);
         }
     }
@@ -332,7 +332,7 @@ struct TrFragAddr16 {
 #pragma unroll
             for (int rd = 0; rd < 2; ++rd) {
                 const int rl = 8 * g + q + 4 * rd;                       // row within the 32-row k-step
-                const int sw = (rl & 7) ^ ((rl >> 3) & 3);
+                const int sw = swz_row(rl);
                 base[hf][rd] = sub * 4096 + rl * 64 + ((chunk ^ sw) << 3) + (m & 7);
             }
         }
