@@ -116,8 +116,9 @@ def assert_parity_vs_noise(gpu, ref, ref_perturbed, name="", factor=1.5, cap_rms
     ten elements above it, else 1 - 10 / size (on a 1280-element gain gradient p99.9 IS the largest element, whose
     ratio between two noise realisations is not bounded by 1.5).  Absolute caps keep the check from becoming vacuous:
     rms <= cap_rms always; the maximum <= cap_max unless the noise floor's own maximum is that large (weight gradients
-    of a few hundred tokens have such elements: sums of few terms), in which case it may exceed the floor's by 50 % (the
-    largest of 10^7 heavy-tailed ratios differs that much between two realisations).  A tensor that no rounding
+    of a few hundred tokens have such elements: sums of few terms), in which case it may be twice the floor's (the
+    largest of 10^7 heavy-tailed ratios differs by up to 1.6 x between two realisations in the runs seen; the rms and
+    the quantile, which are stable statistics, stay bound at `factor`).  A tensor that no rounding
     touches (a bias gradient that is a plain column sum of the upstream gradient) has a noise floor of exactly zero:
     it passes when every element is within the fp32 tolerance."""
     e, f = rel_err(gpu, ref), rel_err(ref_perturbed, ref)
@@ -130,5 +131,5 @@ def assert_parity_vs_noise(gpu, ref, ref_perturbed, name="", factor=1.5, cap_rms
     if em <= TOL_F32:
         return msg
     assert er <= factor * fr and eq <= factor * fq and em <= 2 * factor * fm, msg
-    assert er <= cap_rms and em <= max(cap_max, 1.5 * fm), msg
+    assert er <= cap_rms and em <= max(cap_max, 2.0 * fm), msg
     return msg
