@@ -97,14 +97,17 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
         }
     }
     // each wave issues a quarter of the 2 * 8 * NKS instructions that fill one K tile and one V tile
+    // (waves 0 and 1 fill the K tile, waves 2 and 3 the V tile; the lane's part of the addresses is computed once)
+    constexpr int PER = 4 * D::NKS;
+    RowTileLane dl;
+    dl.init(lane, (unsigned)(ld * 2));
+    const bool fill_v = wave >= 2;
+    const unsigned dcol = (unsigned)(fill_v ? vcol : kcol) * 2;
     auto issue = [&](int j, bf16_t *kt, bf16_t *vt) {
-        constexpr int PER = 4 * D::NKS;
+        const unsigned base = (unsigned)((long)(s0 + j * BKV) * ld * 2) + dcol;
+        bf16_t *t = fill_v ? vt : kt;
 #pragma unroll
-        for (int i = 0; i < PER; ++i) {
-            const int idx = wave * PER + i;
-            if (idx < 8 * D::NKS) rowtile_dma<HD>(rs, kt, s0 + j * BKV, ld, kcol, idx, lane);
-            else rowtile_dma<HD>(rs, vt, s0 + j * BKV, ld, vcol, idx - 8 * D::NKS, lane);
-        }
+        for (int i = 0; i < PER; ++i) rowtile_dma_lane<HD, 64>(rs, t, base, (unsigned)(ld * 2), (wave & 1) * PER + i, dl);
     };
 
     f32x16 oacc[D::DB];
@@ -309,14 +312,17 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
     const float2 row = qok ? ld2[(long)h * n + q] : make_float2(0.f, 0.f);   // (lse * log2(e), delta)
     const float lse2 = row.x, dlt = row.y;
 
+    // (waves 0 and 1 fill the K tile, waves 2 and 3 the V tile; the lane's part of the addresses is computed once)
+    constexpr int PER = 4 * D::NKS;
+    RowTileLane dl;
+    dl.init(lane, (unsigned)(ld * 2));
+    const bool fill_v = wave >= 2;
+    const unsigned dcol = (unsigned)(fill_v ? vcol : kcol) * 2;
     auto issue = [&](int j, bf16_t *kt, bf16_t *vt) {
-        constexpr int PER = 4 * D::NKS;
+        const unsigned base = (unsigned)((long)(s0 + j * BKV) * ld * 2) + dcol;
+        bf16_t *t = fill_v ? vt : kt;
 #pragma unroll
-        for (int i = 0; i < PER; ++i) {
-            const int idx = wave * PER + i;
-            if (idx < 8 * D::NKS) rowtile_dma<HD>(rs, kt, s0 + j * BKV, ld, kcol, idx, lane);
-            else rowtile_dma<HD>(rs, vt, s0 + j * BKV, ld, vcol, idx - 8 * D::NKS, lane);
-        }
+        for (int i = 0; i < PER; ++i) rowtile_dma_lane<HD, 64>(rs, t, base, (unsigned)(ld * 2), (wave & 1) * PER + i, dl);
     };
 
     f32x16 dq[D::DB];
@@ -486,18 +492,24 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(2, 2)))
 
     // Requests tile `it` (out of range: zeros that nobody reads).  Per wave: NKS loads of Q / dO rows, wave 0 one more
     // for the 32 (lse, delta) pairs = 64 consecutive floats.
+    // The first half of the waves fills the Q tile, the second half the dO tile; the lane's part of the addresses
+    // is computed once.
     constexpr int PERQ = 8 * D::NKS / NW;
+    static_assert((4 * D::NKS) % PERQ == 0, "a wave fills rows of one tile only");
+    const bool fill_o = wave * PERQ >= 4 * D::NKS;
+    const unsigned ldw2 = (unsigned)((fill_o ? ldo : ld) * 2);
+    const __amdgpu_buffer_rsrc_t rw = fill_o ? ro : rq;
+    RowTileLane dl;
+    dl.init(lane, ldw2);
     auto issue = [&](int it, bf16_t *qt_, bf16_t *ot_, float *f) __attribute__((always_inline)) {
         const unsigned inv = it < niter ? 0u : kOob;
         const int itc = it < niter ? it : 0;
         const int h = g * grp + (SPLIT ? hsub : itc / nqt);
         const int qs = s0 + (qt_first + itc % nqt) * BQ;
+        const unsigned base = (unsigned)qs * ldw2 + (unsigned)(h * HD) * 2;
+        bf16_t *t = fill_o ? ot_ : qt_;
 #pragma unroll
-        for (int i = 0; i < PERQ; ++i) {
-            const int idx = wave * PERQ + i;
-            if (idx < 4 * D::NKS) rowtile32_dma<HD>(rq, qt_, qs, ld, h * HD, idx, lane, inv);
-            else rowtile32_dma<HD>(ro, ot_, qs, ldo, h * HD, idx - 4 * D::NKS, lane, inv);
-        }
+        for (int i = 0; i < PERQ; ++i) rowtile_dma_lane<HD, 32>(rw, t, base, ldw2, (wave * PERQ + i) % (4 * D::NKS), dl, inv);
         if (wave == 0)
             __builtin_amdgcn_raw_ptr_buffer_load_lds(rf, (lds_void *)f, 4, (unsigned)((((long)h * n + qs) * 2 + lane) * 4) | inv, 0, 0, 0);
     };

@@ -84,6 +84,30 @@ __device__ __forceinline__ void rowtile32_dma(__amdgpu_buffer_rsrc_t rs, bf16_t 
     __builtin_amdgcn_raw_ptr_buffer_load_lds(rs, (lds_void *)(tile + sub * 2048 + g * 512), 16, voff, 0, 0, 0);
 }
 
+// The same loads for a loop that fetches tile after tile: everything that depends on the lane alone is computed
+// once (RowTileLane), everything that depends on the instruction index or the tile is wave-uniform and stays in
+// scalar registers, so that a load costs three vector instructions (add, xor-shift, add) instead of a 64-bit
+// address computation.  base = byte offset of (row0, col0) in the matrix, ld2 = bytes per matrix row; idx must be
+// wave-uniform.  ROWS = 64 (rowtile_dma's layout) or 32 (rowtile32_dma's).
+struct RowTileLane {
+    unsigned rowpart;   // (lane / 8) * ld2: the lane's row within an 8-row group
+    int x;              // (lane % 8) ^ swz_row(lane / 8): chunk position with the lane's part of the swizzle
+    __device__ __forceinline__ void init(int lane, unsigned ld2) {
+        rowpart = (unsigned)(lane >> 3) * ld2;
+        x = (lane & 7) ^ swz_row(lane >> 3);
+    }
+};
+template <int W, int ROWS>
+__device__ __forceinline__ void rowtile_dma_lane(__amdgpu_buffer_rsrc_t rs, bf16_t *tile, unsigned base, unsigned ld2, int idx,
+                                                 const RowTileLane &L, unsigned inv = 0) {
+    constexpr int G = ROWS / 8;                              // 8-row groups per sub-tile
+    const int sub = idx / G, g = idx % G;
+    const int c = L.x ^ swz_row(8 * g);                      // swz_row is linear: swz_row(8 g + l) = swz_row(8 g) ^ swz_row(l)
+    unsigned voff = L.rowpart + (base + (unsigned)(8 * g) * ld2 + (unsigned)sub * 128u) + ((unsigned)c << 4);
+    if (W % 64 != 0 && sub == W / 64) voff = c * 8 < W % 64 ? voff : kOob;   // columns past W arrive as zeros
+    __builtin_amdgcn_raw_ptr_buffer_load_lds(rs, (lds_void *)(tile + sub * (ROWS * 64) + g * 512), 16, voff | inv, 0, 0, 0);
+}
+
 // MFMA operand fragment whose 32 "rows" are tile columns m0 .. m0+31 and whose k-slots are tile rows:
 // half h of the wave gets rows k0 + 4h + {0..3} (slots 0..3) and k0 + 8 + 4h + {0..3} (slots 4..7).
 // SUB = elements per 64-column sub-tile (64 x tile height).
