@@ -109,6 +109,17 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
 #pragma unroll
         for (int i = 0; i < PER; ++i) rowtile_dma_lane<HD, 64>(rs, t, base, (unsigned)(ld * 2), (wave & 1) * PER + i, dl);
     };
+    // The same loads in KST portions, placed between the MFMAs of the S product of the tile before: a direct-to-LDS
+    // load occupies the wave's issue slot for tens of cycles, which the MFMAs already queued cover.  A tile past the
+    // end is requested out of range (zeros that nobody reads), so the loop body has no branch.
+    auto issue_part = [&](int ks, int j, bf16_t *kt, bf16_t *vt) __attribute__((always_inline)) {
+        const unsigned base = (unsigned)((long)(s0 + j * BKV) * ld * 2) + dcol;
+        const unsigned inv = j < nkt ? 0u : kOob;
+        bf16_t *t = fill_v ? vt : kt;
+#pragma unroll
+        for (int i = ks * PER / D::KST; i < (ks + 1) * PER / D::KST; ++i)
+            rowtile_dma_lane<HD, 64>(rs, t, base, (unsigned)(ld * 2), (wave & 1) * PER + i, dl, inv);
+    };
 
     f32x16 oacc[D::DB];
 #pragma unroll
@@ -118,7 +129,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
     float m = -INFINITY, l = 0.f;
     const int q = q0 + lrow;
 
-    auto compute = [&](int j, const bf16_t *kt, const bf16_t *vt) {
+    auto compute = [&](int j, const bf16_t *kt, const bf16_t *vt, bf16_t *kn, bf16_t *vn) {
         // S^T[key][q] for the 64 keys of the tile: two 32-key blocks (two independent accumulation chains); the
         // K fragments of k-step ks + 1 are read while the MFMAs of k-step ks run
         f32x16 st[2];
@@ -141,8 +152,10 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
             }
             st[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[ks & 1][0], qf[ks], st[0], 0, 0, 0);
             st[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[ks & 1][1], qf[ks], st[1], 0, 0, 0);
+            issue_part(ks, j + 1, kn, vn);
             __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
             __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);
+            __builtin_amdgcn_sched_group_barrier(0x020, (PER + D::KST - 1) / D::KST, 0);
         }
         // mask (only tiles that touch the diagonal or the end of the sequence: wave-uniform test), row
         // maximum on the raw scores (one query per lane; the other half-wave holds the other keys),
@@ -203,11 +216,9 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
     issue(0, K0, V0);
     dma_publish_barrier();
     for (int j = 0; j < nkt; j += 2) {
-        if (j + 1 < nkt) issue(j + 1, K1, V1);
-        compute(j, K0, V0);
+        compute(j, K0, V0, K1, V1);
         dma_publish_barrier();
-        if (j + 2 < nkt) issue(j + 2, K0, V0);
-        if (j + 1 < nkt) compute(j + 1, K1, V1);
+        if (j + 1 < nkt) compute(j + 1, K1, V1, K0, V0);
         dma_publish_barrier();
     }
 
@@ -324,6 +335,17 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
 #pragma unroll
         for (int i = 0; i < PER; ++i) rowtile_dma_lane<HD, 64>(rs, t, base, (unsigned)(ld * 2), (wave & 1) * PER + i, dl);
     };
+    // The same loads in KST portions, placed between the MFMAs of the S product of the tile before: a direct-to-LDS
+    // load occupies the wave's issue slot for tens of cycles, which the MFMAs already queued cover.  A tile past the
+    // end is requested out of range (zeros that nobody reads), so the loop body has no branch.
+    auto issue_part = [&](int ks, int j, bf16_t *kt, bf16_t *vt) __attribute__((always_inline)) {
+        const unsigned base = (unsigned)((long)(s0 + j * BKV) * ld * 2) + dcol;
+        const unsigned inv = j < nkt ? 0u : kOob;
+        bf16_t *t = fill_v ? vt : kt;
+#pragma unroll
+        for (int i = ks * PER / D::KST; i < (ks + 1) * PER / D::KST; ++i)
+            rowtile_dma_lane<HD, 64>(rs, t, base, (unsigned)(ld * 2), (wave & 1) * PER + i, dl, inv);
+    };
 
     f32x16 dq[D::DB];
 #pragma unroll
@@ -331,7 +353,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
 #pragma unroll
         for (int r = 0; r < 16; ++r) dq[i][r] = 0.f;
 
-    auto compute = [&](int j, const bf16_t *kt, const bf16_t *vt) {
+    auto compute = [&](int j, const bf16_t *kt, const bf16_t *vt, bf16_t *kn, bf16_t *vn) {
         const int key0 = s0 + j * BKV + 4 * half;
 #pragma unroll
         for (int kb = 0; kb < 2; ++kb) {
@@ -343,6 +365,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
                 const int off = (ks / 4) * 4096 + lds_off(kb * 32 + lrow, (ks % 4) * 2 + half);
                 st = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*(const bf16x8 *)(kt + off), qf[ks], st, 0, 0, 0);
                 dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*(const bf16x8 *)(vt + off), dof[ks], dp, 0, 0, 0);
+                if (kb == 0) issue_part(ks, j + 1, kn, vn);
             }
             // rows past the end of the sequence have zero Q, dO, lse and delta (dS = 0 there without a mask)
             const int kfirst = s0 + j * BKV + kb * 32;
@@ -371,11 +394,9 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
     issue(0, K0, V0);
     dma_publish_barrier();
     for (int j = 0; j < nkt; j += 2) {
-        if (j + 1 < nkt) issue(j + 1, K1, V1);
-        compute(j, K0, V0);
+        compute(j, K0, V0, K1, V1);
         dma_publish_barrier();
-        if (j + 2 < nkt) issue(j + 2, K0, V0);
-        if (j + 1 < nkt) compute(j + 1, K1, V1);
+        if (j + 1 < nkt) compute(j + 1, K1, V1, K0, V0);
         dma_publish_barrier();
     }
     if (!qok) return;
