@@ -120,6 +120,12 @@ def kernel_table(prof, prof_steps, attn_flops):
     return kernels
 
 
+def progress(args, what):
+    """One line on stderr per phase in --dispatch-only mode, so that a profiler run that stops shows where."""
+    if getattr(args, "dispatch_only", False):
+        print(f"[bench] {what}", file=sys.stderr, flush=True)
+
+
 def profile_steps(torch, B, fn, steps):
     B.profile_enable(1)
     for _ in range(steps):
@@ -166,10 +172,16 @@ def bench_kd_step(name, args, torch, B, wl, dev, side):
             B.k_copy(src, dst)
         torch.cuda.synchronize()
         del src, dst
+    progress(args, f"{name}: inputs and weights resident, first launch next")
     for _ in range(args.warmup):
         step()
+    torch.cuda.synchronize()
+    progress(args, f"{name}: warm-up done")
     sec_step, out = timed(torch, step, args.steps)
     loss = float(out["loss"].item())
+    progress(args, f"{name}: timed steps done")
+    if args.dispatch_only:
+        return {"workload": work.name, "n_tokens": n, "ms_per_step": 1e3 * sec_step, "loss": loss}
     sec_teacher, _ = timed(torch, teacher, args.steps)
     sec_student, _ = timed(torch, student, args.steps)
     sec_kd = None
@@ -337,9 +349,15 @@ def bench_secondary(name, args, torch, B, wl, dev):
         att = (a, 2.5 * a)
         desc = (f"{work.name}: vision-encoder section forward+backward, {n} packed patch tokens, {batch.n_seqs} image samples "
                 f"(max {batch.max_seqlen}), {describe(cfg)}, bidirectional")
+    progress(args, f"{name}: inputs and weights resident, first launch next")
     for _ in range(args.warmup):
         fn()
+    torch.cuda.synchronize()
+    progress(args, f"{name}: warm-up done")
     sec, _ = timed(torch, fn, args.steps)
+    progress(args, f"{name}: timed steps done")
+    if args.dispatch_only:
+        return {"workload": work.name, "n_tokens": n, "ms_per_step": 1e3 * sec}
     prof_steps = min(args.steps, 2)
     prof = profile_steps(torch, B, fn, prof_steps)
     return {"workload": desc, "n_tokens": n, "ms_per_step": 1e3 * sec, "tokens_per_s": n / sec,
@@ -431,6 +449,9 @@ def main():
     ap.add_argument("--cpu-sample-tokens", type=int, default=0, help="0: 1024 for c5, 2048 for c2")
     ap.add_argument("--step-only", action="store_true",
                     help="skip the side measurements (KD head alone, teacher sweep, AdamW, references): for profiler runs of the step")
+    ap.add_argument("--dispatch-only", action="store_true",
+                    help="run the warm-up and the timed steps of one workload and print a short line: no per-kernel "
+                         "events, no side measurements (for profiler counter runs, which only need the dispatches)")
     ap.add_argument("--copy-calibration", type=int, default=0, metavar="MIB",
                     help="also run the library's copy kernel 3x on MIB MiB (reference dispatch for counter runs)")
     args = ap.parse_args()
@@ -447,6 +468,7 @@ def main():
         print("bench.py needs a GPU", file=sys.stderr)
         sys.exit(2)
     B.lib()
+    progress(args, "library loaded, GPU visible")
     dev = "cuda"
     kd_metric = "KD step tokens/s (teacher fwd + student fwd+bwd + fused KL loss), 1 GPU"
 
@@ -462,6 +484,13 @@ def main():
             return bench_kd_step(name, args, torch, B, wl, dev, side=(name == "c2"))
         return bench_secondary(name, args, torch, B, wl, dev)
 
+    if args.dispatch_only:
+        if args.workload == "all":
+            print("--dispatch-only needs one --workload", file=sys.stderr)
+            sys.exit(2)
+        args.no_cpu_baseline = True
+        print(json.dumps(run_one(args.workload, True)))
+        return
     if args.workload != "all":
         res = run_one(args.workload, True)
         metric = kd_metric if args.workload in ("c2", "c5") else res["workload"].split(":")[1].split(",")[0].strip() + " tokens/s, 1 GPU"

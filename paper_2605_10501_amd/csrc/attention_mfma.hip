@@ -506,7 +506,9 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(2, 2)))
                 for (int i = 0; i < 8; ++i) kf[ks][i] = (bf16_t)0.f;
         }
     }
-    // query tiles that see this key block
+    // query tiles that see this key block.  They are walked from the last one down: the workgroups of a (sequence, head)
+    // that run at the same time on an XCD (neighbouring key blocks) then read the same Q / dO rows at the same time, one
+    // fetch into L2 serving all of them, whereas walks that start at each block's own first tile are staggered.
     const int qt_first = CAUSAL ? kblk / BQ : 0;
     const int nqt = (s1 - s0 + BQ - 1) / BQ - qt_first;
     const int niter = SPLIT ? nqt : nqt * grp;
@@ -526,7 +528,7 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(2, 2)))
         const unsigned inv = it < niter ? 0u : kOob;
         const int itc = it < niter ? it : 0;
         const int h = g * grp + (SPLIT ? hsub : itc / nqt);
-        const int qs = s0 + (qt_first + itc % nqt) * BQ;
+        const int qs = s0 + (qt_first + nqt - 1 - itc % nqt) * BQ;
         const unsigned base = (unsigned)qs * ldw2 + (unsigned)(h * HD) * 2;
         bf16_t *t = fill_o ? ot_ : qt_;
 #pragma unroll
@@ -546,7 +548,7 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(2, 2)))
     auto compute = [&](auto which, int it, const bf16_t *qt_, const bf16_t *ot_, const float *f) __attribute__((always_inline)) {
         constexpr int WHICH = decltype(which)::value;
         constexpr bool DK = WHICH >= 1, BOTH = WHICH == 2;
-        const int qs = s0 + (qt_first + it % nqt) * BQ;
+        const int qs = s0 + (qt_first + nqt - 1 - it % nqt) * BQ;
         if (CAUSAL && qs + BQ - 1 < kw0) return;            // every query of the tile precedes every key of the wave
         f32x16 st, dp;
 #pragma unroll
