@@ -7,7 +7,7 @@ from oracle import ops, round_bf16, identity
 from oracle.attention import attention_bwd, attention_fwd
 from paper_2605_10501_amd import binding as B
 from paper_2605_10501_amd import workloads as wl
-from parity import TOL_BF16, TOL_F32, assert_parity
+from parity import assert_parity_rows, TOL_BF16, TOL_F32, assert_parity
 
 pytestmark = pytest.mark.gpu
 DTYPES = [torch.bfloat16, torch.float32]
@@ -171,6 +171,11 @@ ATT_CASES = [  # nq, nkv, hd, cu, scale of q/k
     (2, 2, 80, [0, 130, 300], 1.0),
     (8, 2, 128, [0, 257, 321], 1.0),
     (4, 1, 128, [0, 300], 4.0),       # sharp softmax: the online rescaling really works
+    # workgroup -> (sequence, head, tile) mapping: head counts with gcd(heads, 8) = 1, 2, 4 (tile levels striped over
+    # 8, 4, 2 XCDs in serpentine order) and sequences longer than one chunk of levels, next to short and empty ones
+    (3, 1, 64, [0, 2300, 2450, 2451], 1.0),
+    (6, 2, 64, [0, 1100, 1100, 2301], 1.0),
+    (12, 2, 128, [0, 1300, 1557], 1.0),
 ]
 
 
@@ -193,7 +198,11 @@ def test_attention_forward_backward(dtype, causal, nq, nkv, hd, cu, sharp):
     o_ref, lse_ref = attention_fwd(q, k, v, cu, causal, return_lse=True)
     o_ref = rnd(o_ref)
     o, lse = B.k_attention_forward(qkv, batch, nq, nkv, hd, causal)
-    assert_parity(o, o_ref.reshape(n, -1), tol, "o")
+    # sequences of more than a few hundred tokens: the per-row error floor (the rows of a causal sequence see 1 .. L
+    # keys and differ in scale accordingly; see assert_parity_rows), as in the full-shape tests.  It answers the
+    # rounding of P to bf16, which the fp32 path does not have: fp32 keeps the tensor-wide floor
+    cmp = assert_parity_rows if dtype == torch.bfloat16 and max(np.diff(cu)) > 512 else assert_parity
+    cmp(o, o_ref.reshape(n, -1), tol, "o")
     assert_parity(lse, lse_ref, TOL_F32 if dtype == torch.float32 else 1e-3, "lse")
     # the backward kernel on its own: it is handed the oracle's stored output and log-sum-exp, so both
     # sides start from identical inputs (forward -> backward chains are covered at section level)
@@ -206,7 +215,7 @@ def test_attention_forward_backward(dtype, causal, nq, nkv, hd, cu, sharp):
     ref = np.concatenate([dq.reshape(n, -1), dk.reshape(n, -1), dv.reshape(n, -1)], axis=1)
     dqkv = B.k_attention_backward(qkv, o_in, lse_in, d_o, batch, nq, nkv, hd, causal)
     for name, sl in [("dq", slice(0, nq * hd)), ("dk", slice(nq * hd, (nq + nkv) * hd)), ("dv", slice((nq + nkv) * hd, None))]:
-        assert_parity(dqkv[:, sl], rnd(ref[:, sl]), tol, name)
+        cmp(dqkv[:, sl], rnd(ref[:, sl]), tol, name)
 
 
 def test_mfma_probe_counts_what_it_claims():
