@@ -540,10 +540,12 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(2, 2)))
     const bf16_t *vrow = Vs + (wave >> 1) * VS;             // the 64-key row tile holding this wave's keys
     const int vr = (wave & 1) * 32 + lrow;
     // One pass over the query tiles accumulates dV (WHICH = 0: needs S only), dK (1: needs S and dP) or both
-    // (2).  With wide heads the two accumulator sets do not fit 256 registers: two passes (0 then 1) cost one
-    // extra S product and a second round of exponentials per tile but halve the accumulators, which is what
-    // lets two waves share a SIMD.  Heads of at most 96 columns fit both sets: one pass.
-    constexpr bool ONE_PASS = D::DB <= 3;
+    // (2).  Both accumulator sets are kept (one pass) for every head_dim.  At head_dim 128 that is 128 accumulator
+    // registers and the kernel spills about 22 of its 256 registers, which was measured against the alternative that
+    // fits: two passes (0 then 1) with one accumulator set, one extra S product and a second round of exponentials per
+    // tile.  One pass is 11-13 % faster at the c5 / c2 student shapes (3.62 -> 3.21 ms, 0.51 -> 0.465 ms per layer).
+    // The two-pass code path stays selectable here.
+    constexpr bool ONE_PASS = true;
     f32x16 acc[D::DB], acc2[ONE_PASS ? D::DB : 1];          // acc2: dV when both are accumulated (acc is dK then)
     auto compute = [&](auto which, int it, const bf16_t *qt_, const bf16_t *ot_, const float *f) __attribute__((always_inline)) {
         constexpr int WHICH = decltype(which)::value;
