@@ -218,6 +218,16 @@ def test_attention_forward_backward(dtype, causal, nq, nkv, hd, cu, sharp):
         cmp(dqkv[:, sl], rnd(ref[:, sl]), tol, name)
 
 
+@pytest.mark.parametrize("nbytes", [16, 16 * 1023, 16 * (4096 * 4 + 5), (64 << 20) + 48])
+def test_reference_copy_kernel_copies_every_byte(nbytes):
+    # chunk per workgroup, four loads in flight per thread: sizes below one chunk, with a ragged tail, and many chunks
+    src = torch.randint(0, 256, (nbytes,), dtype=torch.uint8, device="cuda")
+    dst = torch.zeros(nbytes + 64, dtype=torch.uint8, device="cuda")
+    B.k_copy(src, dst[:nbytes])
+    torch.cuda.synchronize()
+    assert torch.equal(dst[:nbytes], src) and int(dst[nbytes:].sum()) == 0
+
+
 def test_mfma_probe_counts_what_it_claims():
     # every accumulator element gains (row % 4) / 4 per MFMA; a lane's 16 rows cover each residue 4 times
     sink = torch.zeros(4 * 512, dtype=torch.float32, device="cuda")
